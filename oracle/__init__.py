@@ -1,0 +1,17 @@
+"""fp64 CPU oracle for AdamA -- test infrastructure only.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this
+package; the product package never does.
+"""
+from .adama_oracle import (  # noqa: F401
+    OracleState,
+    alg1_step,
+    apply,
+    begin_step,
+    bf16_to_f64,
+    build,
+    ddp_combine,
+    f16_to_f64,
+    fold,
+    lib_path,
+)
