@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the AdamA hot path (decay + N x per-layer fold + update) on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|c1]
+
+A "step" is one whole mini-batch of the workload through libadama: adama_begin_step over all state,
+then for each of the N micro-batches one adama_fold_multi launch per layer in backward order, then
+adama_apply.  All inputs (theta, m, v and one micro-batch's worth of per-layer gradients, each layer
+at its own address) are resident in HBM before the clock starts; the timed region contains only
+libadama launches.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+
+def algorithmic_bytes_per_step(w) -> int:
+    """decay 16 B/param + N folds of (16 + grad bytes) B/param + update 16 B/param."""
+    return (16 + w.N * (16 + w.grad_bytes) + 16) * w.P
+
+
+def cpu_baseline(w, budget_s: float = 15.0) -> dict:
+    """The fp64 oracle, as it stands, timed on this host over whole layers of the same workload
+    (one full mini-batch each: decay, N folds, update) until about `budget_s` seconds are used."""
+    import numpy as np
+
+    import oracle
+    import synth
+
+    gd = None if w.gdtype == "f32" else w.gdtype
+    spent, params, layers_done = 0.0, 0, []
+    order = sorted(range(len(w.layers)), key=lambda li: -w.layer_elems(li))
+    # start from a mid-sized layer: the largest one alone could exceed the budget
+    order = [li for li in order if w.layer_elems(li) <= 40_000_000] or order[-1:]
+    for li in order:
+        if spent >= budget_s:
+            break
+        for ti in w.layers[li]:
+            n = w.tensors[ti].n
+            theta = synth.fill_host(w.theta_spec(ti), "f32", n).astype(np.float64)
+            m = np.zeros(n)
+            v = np.zeros(n)
+            grads = [synth.fill_host(w.grad_spec(1, i, ti), w.gdtype, n) for i in range(min(w.N, 2))]
+            t0 = time.perf_counter()
+            oracle.begin_step(m, v, w.beta1, w.beta2)
+            for i in range(w.N):
+                oracle.fold(m, v, grads[i % len(grads)], w.N, w.beta1, w.beta2, gdtype=gd)
+            oracle.apply(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1)
+            spent += time.perf_counter() - t0
+            params += n
+        layers_done.append(li)
+    per_param = 16 + w.N * (16 + w.grad_bytes) + 16
+    return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "params_per_s": round(params / spent, 1),
+            "sample": f"{len(layers_done)} whole layer(s) of {w.name} ({params} params), one full mini-batch "
+                      f"each (decay + {w.N} folds + update) in {spent:.1f} s, single thread, fp64"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+
+    import synth
+    from paper_2305_19982_amd import binding
+    from paper_2305_19982_amd.harness import SimulatedBackward
+    from synth import configs
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 1
+    binding.load()                      # fails loudly if libadama.so is missing
+    w = configs.FULL[args.workload]()
+    hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model")
+    sh = hb.stream_handle
+    # ---- resident inputs: theta0 and one micro-batch of gradients, every layer at its own address ----
+    for t in w.tensors:
+        synth.fill_device(hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, sh)
+        synth.fill_device(hb.grad_ptr(t.index), w.grad_spec(1, 0, t.index), w.gdtype, t.n, sh)
+    hb.synchronize()
+
+    # the fold launches of the dominant kernel (big-chunk variant): layers of at least 2^22 elements
+    big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= (1 << 22)}
+    fold_events = []
+
+    def one_step(timed: bool) -> None:
+        hb.begin_step(w.beta1, w.beta2)
+        for _ in range(w.N):
+            for li in w.backward_layers():
+                if timed and li in big_layers:
+                    e0 = torch.cuda.Event(enable_timing=True)
+                    e1 = torch.cuda.Event(enable_timing=True)
+                    e0.record(hb.stream)
+                    hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                    e1.record(hb.stream)
+                    fold_events.append((e0, e1, w.layer_elems(li)))
+                else:
+                    hb.fold_layer(li, w.N, w.beta1, w.beta2)
+        hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+
+    for _ in range(args.warmup):
+        one_step(False)
+    hb.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step(False)
+    hb.synchronize()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # ---- live per-launch timing of the dominant kernel, HIP events on the launch stream ----
+    for _ in range(min(2, args.steps)):
+        one_step(True)
+    hb.synchronize()
+    fold_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in fold_events)
+    fold_bytes = sum(n for _, _, n in fold_events) * (16 + w.grad_bytes)
+    launches = len(fold_events)
+    achieved = fold_bytes / (fold_ms * 1e-3) / 1e9 if fold_ms > 0 else 0.0
+
+    step_bytes = algorithmic_bytes_per_step(w)
+    value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "metric": "AdamA fold+apply effective HBM GB/s (algorithmic bytes of decay + N folds + update per second)",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.gdtype == "f32" else f"f32 state, {w.gdtype} gradients",
+        "data": "synthetic",
+        "config": {"workload": w.name, "params": w.P, "tensors": len(w.tensors), "layers": len(w.layers),
+                   "micro_batches": w.N, "grad_dtype": w.gdtype, "bytes_per_step": step_bytes,
+                   "fold_launches_per_step": w.N * len(w.layers)},
+        "params_per_s": round(w.P / (ms_per_step * 1e-3), 1),
+        "param_folds_per_s": round(w.P * w.N / (ms_per_step * 1e-3), 1),
+        "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U=4>",
+                     "launches_timed": launches,
+                     "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
+                     "bytes_per_launch": round(fold_bytes / launches) if launches else None},
+        "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
+                        "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
+                        "whole_model_bytes": w.P * w.grad_bytes},
+    }
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as fh:
+            out["roofline"]["traffic"] = json.load(fh).get("bytes_per_launch")
+    if args.cpu_budget > 0:
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

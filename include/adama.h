@@ -1,0 +1,132 @@
+/*
+ * libadama -- the AdamA (Adam Accumulation) optimizer hot path for AMD MI355X (gfx950).
+ *
+ * AdamA folds every freshly produced gradient tensor straight into Adam's first
+ * and second moments, once per layer per micro-batch, so the gradient buffer can
+ * be released at once instead of being accumulated over the mini-batch (paper,
+ * Sec. 3.1, Alg. 1 red variant and Alg. 2).  One mini-batch is
+ *
+ *     adama_begin_step            m <- beta1 m, v <- beta2 v        (Alg. 2, first line of the loop)
+ *     N x layers x adama_fold*    m += (1-beta1) g, v += (1-beta2) g^2, g = grad/N   (Alg. 2, inner body)
+ *     adama_apply                 bias-corrected parameter update     (Alg. 2, "Update")
+ *
+ * Conventions common to every call
+ *  - All data pointers are DEVICE pointers owned by the caller; `list` arrays of
+ *    descriptors are HOST memory and are consumed before the call returns.
+ *  - m, v, theta are float32.  Gradients are float32, bfloat16 or float16 (adama_dtype).
+ *    Pointers need only their natural element alignment; 16-byte vector access is
+ *    used wherever a tensor's three pointers share the same misalignment.
+ *  - Work is enqueued on `stream` (0 = the null stream).  Nothing is allocated,
+ *    nothing synchronises, the call returns as soon as the launches are queued.
+ *    Stream order is the only ordering: a gradient buffer may be overwritten by
+ *    any later operation on the same stream.
+ *  - A gradient must not overlap m or v; tensors of one list must not overlap.
+ *  - Hyper-parameters are doubles; derived scalars ((1-beta1)/N, (1-beta2)/N^2,
+ *    1-beta^t, ...) are formed in double on the host and rounded to float once.
+ *  - Length 0 / count 0 is a successful no-op.  Errors are reported by the return
+ *    value, with a message available from adama_last_error(); nothing aborts.
+ *    Argument errors are detected before any device work is queued.
+ */
+#ifndef ADAMA_H
+#define ADAMA_H
+
+#include <stddef.h>
+
+#include <hip/hip_runtime_api.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    ADAMA_OK = 0,
+    ADAMA_ERR_INVALID_ARG = 1,        /* null pointer, misaligned pointer, N < 1, t < 1, bad hyper-parameter */
+    ADAMA_ERR_UNSUPPORTED_DTYPE = 2,  /* gradient dtype is not one of adama_dtype */
+    ADAMA_ERR_TOO_LARGE = 3,          /* a tensor is longer than ADAMA_MAX_ELEMS */
+    ADAMA_ERR_HIP = 4                 /* a HIP runtime call failed; text in adama_last_error() */
+} adama_status;
+
+typedef enum { ADAMA_F32 = 0, ADAMA_BF16 = 1, ADAMA_F16 = 2 } adama_dtype;
+
+/* Longest tensor accepted by any call (elements). */
+#define ADAMA_MAX_ELEMS (1ull << 40)
+
+/* One tensor of a fold list: moments and the raw gradient of the micro-batch loss. */
+typedef struct {
+    float *m;          /* device, n floats, read and written */
+    float *v;          /* device, n floats, read and written */
+    const void *grad;  /* device, n elements of the list's gradient dtype, read only */
+    size_t n;
+} adama_tensor;
+
+/* One tensor of a state list (decay / update). theta may be NULL for adama_begin_step_multi. */
+typedef struct {
+    float *theta;      /* device, n floats, read and written by adama_apply_multi */
+    float *m;          /* device, n floats */
+    float *v;          /* device, n floats */
+    size_t n;
+} adama_state;
+
+/* Alg. 2, first line of the while-loop body: once per mini-batch, before its first fold,
+ *     m[k] <- beta1 * m[k],  v[k] <- beta2 * v[k]          k in [0, n)
+ * (the step counter t <- t+1 is the caller's integer).  beta1, beta2 must be finite and >= 0;
+ * values above 1 are accepted because the data-parallel scheme of Sec. 3.3 decays v by
+ * (number of devices) * beta2. */
+adama_status adama_begin_step(float *m, float *v, size_t n, double beta1, double beta2, hipStream_t stream);
+
+/* The same decay over a host list of `count` tensors (theta fields ignored) in as few launches
+ * as the descriptor table allows (ADAMA_MAX_TENSORS_PER_LAUNCH tensors each). */
+adama_status adama_begin_step_multi(const adama_state *list, int count, double beta1, double beta2,
+                                    hipStream_t stream);
+
+/* Alg. 2, inner loop body, for one gradient tensor of one micro-batch:
+ *     g <- grad[k] / N;  m[k] <- m[k] + (1-beta1) g;  v[k] <- v[k] + (1-beta2) g^2
+ * `grad` is the raw gradient of the micro-batch loss (NOT pre-divided by N), stored as `gdt`;
+ * N >= 1 is the number of micro-batches per mini-batch; beta1, beta2 in [0, 1).
+ * The gradient is widened to float32 before scaling and squaring. */
+adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N,
+                        double beta1, double beta2, hipStream_t stream);
+
+/* The fold of Alg. 2 over a whole layer: a ragged host list of `count` tensors, all with gradient
+ * dtype `gdt`, in one launch per ADAMA_MAX_TENSORS_PER_LAUNCH tensors.  Results are bit-identical
+ * to calling adama_fold on each tensor. */
+adama_status adama_fold_multi(const adama_tensor *list, int count, adama_dtype gdt, int N,
+                              double beta1, double beta2, hipStream_t stream);
+
+/* Alg. 2, "Update" (same as Alg. 1), after the last fold of mini-batch t >= 1:
+ *     m_hat <- m[k] / (1 - beta1^t);  v_hat <- v[k] / (1 - beta2^t)
+ *     theta[k] <- theta[k] - lr * m_hat / (sqrt(v_hat) + eps)
+ * m and v are read only.  beta1, beta2 in [0, 1); lr, eps finite, eps >= 0. */
+adama_status adama_apply(float *theta, const float *m, const float *v, size_t n, double lr, double eps,
+                         double beta1, double beta2, long long t, hipStream_t stream);
+
+/* The same update over a host list of `count` tensors. */
+adama_status adama_apply_multi(const adama_state *list, int count, double lr, double eps, double beta1,
+                               double beta2, long long t, hipStream_t stream);
+
+/* Message of the last failing call on this thread ("" if none).  Valid until the next call
+ * on the same thread. */
+const char *adama_last_error(void);
+
+/* Number of tensors one launch's descriptor table holds. */
+#define ADAMA_MAX_TENSORS_PER_LAUNCH 96
+int adama_max_tensors_per_launch(void);
+
+/*
+ * Host-only check of the launch geometry (no device needed, nothing is dereferenced): walks every
+ * (launch, chunk, thread, access) the kernels would issue for `list` and adds 1 to touched[k][e]
+ * for each element e of tensor k an access covers (touched[k] is a host array of list[k].n bytes,
+ * zero-filled by the caller).  op: 0 decay, 1 fold, 2 apply; for op != 1 the three pointers of
+ * each adama_tensor stand for the op's three arrays.  *vector_accesses and *scalar_accesses count
+ * 16-byte and single-element accesses.  Returns ADAMA_ERR_INVALID_ARG if an access would leave a
+ * tensor or a vector access would be misaligned.  Used by the CPU test-suite.
+ */
+adama_status adama_debug_walk(const adama_tensor *list, int count, int op, adama_dtype gdt,
+                              unsigned char *const *touched, unsigned long long *vector_accesses,
+                              unsigned long long *scalar_accesses, int *launches);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ADAMA_H */

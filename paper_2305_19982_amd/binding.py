@@ -1,0 +1,157 @@
+"""Thin ctypes binding of libadama's C ABI (include/adama.h): argument marshalling only.
+
+Every function has the name and argument order of its C counterpart.  Device
+arrays are passed as integer device addresses or as objects with `.data_ptr()`
+(e.g. torch tensors, used here only as owners of device memory); `stream` is a
+raw `hipStream_t` value such as `torch.cuda.Stream().cuda_stream` (0 = null
+stream).  A non-zero status raises AdamaError carrying adama_last_error().
+
+There is no CPU fallback: if the library has not been built, importing this
+module's functions fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+from . import build as _build
+
+F32, BF16, F16 = 0, 1, 2
+DTYPES = {"f32": F32, "bf16": BF16, "f16": F16, F32: F32, BF16: BF16, F16: F16}
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED_DTYPE, ERR_TOO_LARGE, ERR_HIP = range(5)
+STATUS_NAMES = {OK: "ADAMA_OK", ERR_INVALID_ARG: "ADAMA_ERR_INVALID_ARG",
+                ERR_UNSUPPORTED_DTYPE: "ADAMA_ERR_UNSUPPORTED_DTYPE", ERR_TOO_LARGE: "ADAMA_ERR_TOO_LARGE",
+                ERR_HIP: "ADAMA_ERR_HIP"}
+
+
+class AdamaError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+        self.message = message
+
+
+class adama_tensor(ctypes.Structure):
+    _fields_ = [("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
+class adama_state(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load() -> ctypes.CDLL:
+    """Load libadama.so (building it first only if it does not exist at all)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_libadama()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, sz, dbl, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_double, ctypes.c_int, ctypes.c_longlong
+    lib.adama_begin_step.argtypes = [vp, vp, sz, dbl, dbl, vp]
+    lib.adama_begin_step_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, vp]
+    lib.adama_fold.argtypes = [vp, vp, vp, i32, sz, i32, dbl, dbl, vp]
+    lib.adama_fold_multi.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, dbl, dbl, vp]
+    lib.adama_apply.argtypes = [vp, vp, vp, sz, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adama_apply_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adama_debug_walk.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, ctypes.POINTER(vp),
+                                     ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_ulonglong),
+                                     ctypes.POINTER(i32)]
+    for name in ("adama_begin_step", "adama_begin_step_multi", "adama_fold", "adama_fold_multi", "adama_apply",
+                 "adama_apply_multi", "adama_debug_walk"):
+        getattr(lib, name).restype = i32
+    lib.adama_last_error.restype = ctypes.c_char_p
+    lib.adama_last_error.argtypes = []
+    lib.adama_max_tensors_per_launch.restype = i32
+    lib.adama_max_tensors_per_launch.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(x) -> int | None:
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return int(x.data_ptr())
+
+
+def _check(status: int) -> None:
+    if status != OK:
+        raise AdamaError(status, load().adama_last_error().decode("utf-8", "replace"))
+
+
+def adama_last_error() -> str:
+    return load().adama_last_error().decode("utf-8", "replace")
+
+
+def adama_max_tensors_per_launch() -> int:
+    return int(load().adama_max_tensors_per_launch())
+
+
+def tensor_list(entries) -> ctypes.Array:
+    """Host array of adama_tensor from (m, v, grad, n) tuples; reusable across calls."""
+    arr = (adama_tensor * len(entries))()
+    for i, (m, v, g, n) in enumerate(entries):
+        arr[i] = adama_tensor(_ptr(m), _ptr(v), _ptr(g), int(n))
+    return arr
+
+
+def state_list(entries) -> ctypes.Array:
+    """Host array of adama_state from (theta, m, v, n) tuples; reusable across calls."""
+    arr = (adama_state * len(entries))()
+    for i, (th, m, v, n) in enumerate(entries):
+        arr[i] = adama_state(_ptr(th), _ptr(m), _ptr(v), int(n))
+    return arr
+
+
+def adama_begin_step(m, v, n: int, beta1: float, beta2: float, stream: int = 0) -> None:
+    _check(load().adama_begin_step(_ptr(m), _ptr(v), n, beta1, beta2, stream))
+
+
+def adama_begin_step_multi(lst, count: int | None, beta1: float, beta2: float, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = state_list(lst)
+    _check(load().adama_begin_step_multi(lst, len(lst) if count is None else count, beta1, beta2, stream))
+
+
+def adama_fold(m, v, grad, gdt, n: int, N: int, beta1: float, beta2: float, stream: int = 0) -> None:
+    _check(load().adama_fold(_ptr(m), _ptr(v), _ptr(grad), DTYPES.get(gdt, gdt), n, N, beta1, beta2, stream))
+
+
+def adama_fold_multi(lst, count: int | None, gdt, N: int, beta1: float, beta2: float, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = tensor_list(lst)
+    _check(load().adama_fold_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N, beta1,
+                                   beta2, stream))
+
+
+def adama_apply(theta, m, v, n: int, lr: float, eps: float, beta1: float, beta2: float, t: int,
+                stream: int = 0) -> None:
+    _check(load().adama_apply(_ptr(theta), _ptr(m), _ptr(v), n, lr, eps, beta1, beta2, t, stream))
+
+
+def adama_apply_multi(lst, count: int | None, lr: float, eps: float, beta1: float, beta2: float, t: int,
+                      stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = state_list(lst)
+    _check(load().adama_apply_multi(lst, len(lst) if count is None else count, lr, eps, beta1, beta2, t, stream))
+
+
+def adama_debug_walk(entries, op: int, gdt):
+    """Host-only geometry walk.  entries: (a, b, c, n) integer addresses (never dereferenced).
+    Returns (touch counts per tensor as bytearrays, vector accesses, scalar accesses, launches)."""
+    lst = tensor_list(entries)
+    bufs = [(ctypes.c_ubyte * max(1, int(e[3])))() for e in entries]
+    ptrs = (ctypes.c_void_p * max(1, len(entries)))(*[ctypes.addressof(b) for b in bufs])
+    nvec, nsc, nl = ctypes.c_ulonglong(0), ctypes.c_ulonglong(0), ctypes.c_int(0)
+    _check(load().adama_debug_walk(lst, len(entries), op, DTYPES.get(gdt, gdt), ptrs, ctypes.byref(nvec),
+                                   ctypes.byref(nsc), ctypes.byref(nl)))
+    return [bytes(b)[:int(e[3])] for b, e in zip(bufs, entries)], nvec.value, nsc.value, nl.value

@@ -1,0 +1,97 @@
+// Launch geometry shared by the kernels and by the host-side geometry walk.
+//
+// One launch processes up to kMaxTensors tensors.  Each tensor is cut into
+// chunks of `chunk` elements measured in "aligned coordinates": element e of a
+// tensor sits at coordinate pre + e, where pre (0..3) is the number of float32
+// elements by which the tensor's first state array is past a 16-byte boundary.
+// Coordinates that are multiples of 4 therefore fall on 16-byte boundaries of
+// the state arrays, whatever the tensor's start address.  When the other two
+// arrays of the tensor share that misalignment ("co-aligned"), every 4-element
+// group wholly inside the tensor can be moved with 16-byte accesses; the at
+// most one partial group at either end, and tensors that are not co-aligned,
+// are moved element by element.
+#pragma once
+
+#include <stdint.h>
+
+#if defined(__HIPCC__)
+#define ADAMA_HD __host__ __device__ inline
+#else
+#define ADAMA_HD inline
+#endif
+
+namespace adama {
+
+constexpr int kBlock = 256;       // threads per workgroup: four 64-wide wavefronts
+constexpr int kGroup = 4;         // elements per 16-byte float32 access
+constexpr int kMaxTensors = 96;   // descriptors per launch (table lives in the kernel argument block)
+
+enum Op : int { kDecay = 0, kFold = 1, kApply = 2 };
+
+// The three arrays of one tensor.  decay: a=m, b=v.  fold: a=m, b=v, c=grad.  apply: a=theta, b=m, c=v.
+struct Desc {
+    void *a;
+    void *b;
+    const void *c;
+    uint64_t n;
+};
+
+template <int MaxT>
+struct Table {
+    Desc t[MaxT];
+    uint32_t chunk_start[MaxT + 1];   // chunk_start[k] = first chunk of tensor k; [count] = total
+    uint32_t count;
+    uint32_t pad;
+};
+
+// Misalignment of the first state array, in float32 elements (0..3).
+ADAMA_HD uint32_t misalign_elems(const void *a) { return (uint32_t)(((uintptr_t)a >> 2) & (kGroup - 1)); }
+
+// True when b (float32) and c (elements of c_bytes bytes, or unused when c_bytes == 0) reach a
+// 16-byte boundary at the same element index as a does.
+ADAMA_HD bool coaligned(const void *a, const void *b, const void *c, uint32_t c_bytes)
+{
+    uint32_t pre = misalign_elems(a);
+    if ((((uintptr_t)b >> 2) & (kGroup - 1)) != pre) return false;
+    if (c_bytes == 0) return true;
+    uint32_t shift = c_bytes == 4 ? 2 : 1;
+    return (((uintptr_t)c >> shift) & (kGroup - 1)) == pre;
+}
+
+ADAMA_HD uint64_t chunks_of(uint32_t pre, uint64_t n, uint32_t chunk)
+{
+    return n == 0 ? 0 : (pre + n + chunk - 1) / chunk;
+}
+
+// Largest k in [0, count) with start[k] <= c, given start[0] == 0 <= c < start[count].
+// Zero-length tensors (start[k] == start[k+1]) are skipped by the tie rule.
+template <typename StartArray>
+ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t count, uint32_t c)
+{
+    uint32_t lo = 0, hi = count;
+    while (hi - lo > 1) {
+        uint32_t mid = (lo + hi) >> 1;
+        if (start[mid] <= c) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
+// Chunk lc of a tensor covers coordinates [lc*chunk, (lc+1)*chunk).  It is "interior" when the
+// tensor is co-aligned and the whole coordinate range lies inside [pre, pre+n): then every group
+// of the chunk is a full, 16-byte aligned group.
+ADAMA_HD bool chunk_is_interior(bool vec, uint32_t pre, uint64_t n, uint64_t lc, uint32_t chunk)
+{
+    uint64_t lo = lc * chunk;
+    return vec && lo >= pre && lo + chunk <= pre + n;
+}
+
+// How the group at coordinate `coord` (a multiple of 4) is moved: 2 = one 16-byte access per array,
+// 1 = element by element (only elements inside the tensor), 0 = nothing to do.
+ADAMA_HD int group_kind(bool vec, uint32_t pre, uint64_t n, uint64_t coord)
+{
+    if (coord + kGroup <= pre || coord >= pre + n) return 0;
+    if (vec && coord >= pre && coord + kGroup <= pre + n) return 2;
+    return 1;
+}
+
+}  // namespace adama

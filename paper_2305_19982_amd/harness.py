@@ -1,0 +1,147 @@
+"""Simulated backward pass driving libadama the way Alg. 2 of the paper prescribes.
+
+The harness owns theta, m, v for a list of parameter tensors grouped in layers,
+and ONE gradient buffer sized for the largest layer.  For each micro-batch it
+walks the layers in backward order; a caller-supplied producer writes that
+layer's raw gradients into the buffer ("assign memory for g"), one
+adama_fold_multi launch folds the whole layer into m and v, and the buffer is
+free for the next layer as soon as the launch is queued ("release memory for
+g"): stream order is the only synchronisation.  Peak gradient memory is
+therefore the largest layer, not the whole model (Sec. 3.1, last paragraph).
+
+PyTorch is used for device allocations and stream handles only.  All optimizer
+arithmetic happens inside libadama's kernels.
+"""
+from __future__ import annotations
+
+from typing import Callable, Sequence
+
+import torch
+
+from . import binding
+
+_GRAD_BYTES = {"f32": 4, "bf16": 2, "f16": 2}
+
+
+def _round_up(x: int, a: int) -> int:
+    return (x + a - 1) // a * a
+
+
+class SimulatedBackward:
+    """theta/m/v state plus a single reusable per-layer gradient buffer.
+
+    tensor_sizes : number of elements of every parameter tensor
+    layers       : lists of tensor indices, forward order (backward visits them reversed)
+    gdtype       : "f32" | "bf16" | "f16" gradient storage
+    pack         : "aligned"  -> every tensor starts on a 256-byte boundary (separate-allocation like)
+                   "tight"    -> tensors back to back, so starts are generally not 16-byte aligned
+    grad_buffer  : "layer"    -> the AdamA layout: one buffer of the largest layer's size, reused
+                   "model"    -> every layer has its own region (what gradient accumulation must keep);
+                                 only for measurements that want all gradient inputs resident and
+                                 distinct in HBM before the clock starts
+    """
+
+    def __init__(self, tensor_sizes: Sequence[int], layers: Sequence[Sequence[int]], gdtype: str,
+                 device: str = "cuda:0", stream: torch.cuda.Stream | None = None, pack: str = "aligned",
+                 grad_buffer: str = "layer"):
+        if gdtype not in _GRAD_BYTES:
+            raise ValueError(gdtype)
+        binding.load()
+        self.device = torch.device(device)
+        self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        self.gdtype = gdtype
+        self.gbytes = _GRAD_BYTES[gdtype]
+        self.sizes = [int(n) for n in tensor_sizes]
+        self.layers = [list(l) for l in layers]
+        self.t = 0
+        align_elems = 64 if pack == "aligned" else 1          # 64 fp32 = 256 B
+        # ---- persistent state: three flat fp32 arenas with identical tensor offsets ----
+        self.offset = []
+        off = 0
+        for n in self.sizes:
+            self.offset.append(off)
+            off = _round_up(off + n, align_elems)
+        self.arena_elems = max(off, 1)
+        with torch.cuda.stream(self.stream):
+            self.theta = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+            self.m = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+            self.v = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+        # ---- the one gradient buffer: layer-local offsets, reused by every layer ----
+        self.grad_offset = [0] * len(self.sizes)             # element offset inside the buffer
+        largest = 0
+        o = 0
+        for idx in self.layers:
+            if grad_buffer == "layer":
+                o = 0
+            for ti in idx:
+                self.grad_offset[ti] = o
+                o = _round_up(o + self.sizes[ti], align_elems * 4 // self.gbytes if pack == "aligned" else 1)
+            largest = max(largest, o)
+        self.grad_buffer_elems = max(largest, 1)
+        self.grad_buffer = torch.empty(self.grad_buffer_elems * self.gbytes, dtype=torch.uint8, device=self.device)
+        # ---- descriptor lists, built once ----
+        base_t, base_m, base_v = self.theta.data_ptr(), self.m.data_ptr(), self.v.data_ptr()
+        gb = self.grad_buffer.data_ptr()
+        self._fold_lists = []
+        for idx in self.layers:
+            self._fold_lists.append(binding.tensor_list(
+                [(base_m + 4 * self.offset[ti], base_v + 4 * self.offset[ti],
+                  gb + self.gbytes * self.grad_offset[ti], self.sizes[ti]) for ti in idx]))
+        self._state_list = binding.state_list(
+            [(base_t + 4 * o, base_m + 4 * o, base_v + 4 * o, n) for o, n in zip(self.offset, self.sizes)])
+
+    # ---- memory accounting (a4) ----
+    @property
+    def peak_grad_bytes(self) -> int:
+        """Bytes of gradient storage that ever exist at once: the single buffer."""
+        return self.grad_buffer_elems * self.gbytes
+
+    @property
+    def whole_model_grad_bytes(self) -> int:
+        """What plain gradient accumulation would have to keep for the whole mini-batch."""
+        return sum(self.sizes) * self.gbytes
+
+    # ---- addresses for producers and checks ----
+    @property
+    def stream_handle(self) -> int:
+        return self.stream.cuda_stream
+
+    def grad_ptr(self, ti: int) -> int:
+        return self.grad_buffer.data_ptr() + self.gbytes * self.grad_offset[ti]
+
+    def theta_ptr(self, ti: int) -> int:
+        return self.theta.data_ptr() + 4 * self.offset[ti]
+
+    def tensor_view(self, which: str, ti: int) -> torch.Tensor:
+        arena = {"theta": self.theta, "m": self.m, "v": self.v}[which]
+        return arena[self.offset[ti]: self.offset[ti] + self.sizes[ti]]
+
+    # ---- Alg. 2 ----
+    def begin_step(self, beta1: float, beta2: float) -> None:
+        """t <- t+1, m <- beta1 m, v <- beta2 v."""
+        self.t += 1
+        binding.adama_begin_step_multi(self._state_list, None, beta1, beta2, self.stream_handle)
+
+    def fold_layer(self, li: int, N: int, beta1: float, beta2: float) -> None:
+        binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+
+    def micro_batch(self, produce: Callable[[int], None], N: int, beta1: float, beta2: float) -> None:
+        """One backward pass: for each layer, last to first, produce(li) must enqueue on self.stream
+        the writes of that layer's gradients into the buffer; the layer is then folded."""
+        for li in range(len(self.layers) - 1, -1, -1):
+            produce(li)
+            self.fold_layer(li, N, beta1, beta2)
+
+    def apply(self, lr: float, eps: float, beta1: float, beta2: float) -> None:
+        binding.adama_apply_multi(self._state_list, None, lr, eps, beta1, beta2, self.t, self.stream_handle)
+
+    def mini_batch(self, produce: Callable[[int, int], None], N: int, lr: float, eps: float, beta1: float,
+                   beta2: float) -> None:
+        """One full pass of the hot path; produce(micro, li) fills the buffer with layer li's gradients."""
+        self.begin_step(beta1, beta2)
+        for i in range(N):
+            self.micro_batch(lambda li, i=i: produce(i, li), N, beta1, beta2)
+        self.apply(lr, eps, beta1, beta2)
+
+    def synchronize(self) -> None:
+        self.stream.synchronize()

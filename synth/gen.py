@@ -1,0 +1,155 @@
+"""Python front end of the seeded synthetic-input generator (synth_gen.h).
+
+Inputs only: gradient-like and weight-like values.  None of the optimizer's
+arithmetic lives here, and neither the oracle nor the HIP library imports it;
+tests, the harness and the benchmark feed both sides from it.
+
+Host and device builds of the generator produce identical bits for the same
+(spec, element index), so a slice of what the device wrote into a gradient
+buffer can be regenerated on the host for the oracle without reading it back.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+HOST_LIB = os.path.join(_HERE, "libsynth_host.so")
+DEVICE_LIB = os.path.join(_HERE, "libsynth_device.so")
+
+F32, BF16, F16 = 0, 1, 2
+DTYPE_ID = {"f32": F32, "bf16": BF16, "f16": F16}
+DTYPE_BYTES = {"f32": 4, "bf16": 2, "f16": 2}
+_MASK = (1 << 64) - 1
+
+
+class _Spec(ctypes.Structure):
+    _fields_ = [("key", ctypes.c_uint64), ("sigma", ctypes.c_float), ("outlier_scale", ctypes.c_float),
+                ("t_zero", ctypes.c_uint32), ("t_outlier", ctypes.c_uint32), ("t_sub", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
+
+
+@dataclass(frozen=True)
+class Spec:
+    """One stream of synthetic values (see synth_gen.h for the value classes)."""
+    key: int
+    sigma: float
+    p_zero: float = 0.0
+    p_outlier: float = 0.0
+    outlier_scale: float = 10.0
+    p_sub: float = 0.0
+
+    def c_struct(self) -> _Spec:
+        thr = lambda p: min(int(round(p * 2.0 ** 32)), 2 ** 32 - 1)   # noqa: E731
+        return _Spec(self.key & _MASK, self.sigma, self.outlier_scale, thr(self.p_zero),
+                     thr(self.p_outlier), thr(self.p_sub), 0)
+
+
+def mix64(z: int) -> int:
+    z &= _MASK
+    z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & _MASK
+    z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & _MASK
+    return z ^ (z >> 31)
+
+
+def stream_key(seed: int, *ids: int) -> int:
+    """Key of the stream named by (seed, ids...): a chain of 64-bit mixes."""
+    k = mix64(seed + 0x632BE59BD9B4E019)
+    for i in ids:
+        k = mix64(k ^ mix64((int(i) + 0x9E3779B97F4A7C15) & _MASK))
+    return k
+
+
+def unit_uniform(key: int) -> float:
+    """A uniform in [0,1) derived from a key (host side only, e.g. per-tensor sigma draws)."""
+    return (mix64(key ^ 0xA0761D6478BD642F) >> 11) * 2.0 ** -53
+
+
+def log_uniform(key: int, lo: float, hi: float) -> float:
+    return math.exp(math.log(lo) + unit_uniform(key) * (math.log(hi) - math.log(lo)))
+
+
+def build_host(force: bool = False) -> str:
+    src = os.path.join(_HERE, "synth_host.c")
+    hdr = os.path.join(_HERE, "synth_gen.h")
+    if (not force and os.path.exists(HOST_LIB)
+            and os.path.getmtime(HOST_LIB) >= max(os.path.getmtime(src), os.path.getmtime(hdr))):
+        return HOST_LIB
+    tmp = HOST_LIB + f".tmp{os.getpid()}"
+    subprocess.run(["gcc", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-std=c11", "-fPIC",
+                    "-shared", "-o", tmp, src, "-lm"], check=True)
+    os.replace(tmp, HOST_LIB)
+    return HOST_LIB
+
+
+def build_device() -> str:
+    src = os.path.join(_HERE, "synth_device.hip")
+    tmp = DEVICE_LIB + f".tmp{os.getpid()}"
+    subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-ffp-contract=off",
+                    "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+                    "-fPIC", "-shared", "-o", tmp, src], check=True)
+    os.replace(tmp, DEVICE_LIB)
+    return DEVICE_LIB
+
+
+_host = None
+_device = None
+
+
+def _host_lib():
+    global _host
+    if _host is None:
+        _host = ctypes.CDLL(build_host())
+        _host.synth_fill_host.restype = ctypes.c_int
+        _host.synth_fill_host.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                          ctypes.POINTER(_Spec)]
+        _host.synth_mix64_host.restype = ctypes.c_uint64
+        _host.synth_mix64_host.argtypes = [ctypes.c_uint64]
+    return _host
+
+
+def _device_lib():
+    global _device
+    if _device is None:
+        if not os.path.exists(DEVICE_LIB):
+            build_device()
+        _device = ctypes.CDLL(DEVICE_LIB)
+        _device.synth_fill_device.restype = ctypes.c_int
+        _device.synth_fill_device.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
+                                              ctypes.POINTER(_Spec), ctypes.c_void_p]
+    return _device
+
+
+def fill_host(spec: Spec, dtype: str, n: int, first: int = 0) -> np.ndarray:
+    """Elements first .. first+n-1 of the stream: float32 array, or uint16 bit patterns for bf16/f16."""
+    out = np.empty(n, dtype=np.float32 if dtype == "f32" else np.uint16)
+    cs = spec.c_struct()
+    rc = _host_lib().synth_fill_host(out.ctypes.data, DTYPE_ID[dtype], n, first, ctypes.byref(cs))
+    if rc:
+        raise RuntimeError(f"synth_fill_host failed ({rc})")
+    return out
+
+
+def fill_device(ptr: int, spec: Spec, dtype: str, n: int, stream: int, first: int = 0) -> None:
+    """Enqueue a fill of device memory at `ptr` with elements first .. first+n-1 on HIP stream `stream`."""
+    cs = spec.c_struct()
+    rc = _device_lib().synth_fill_device(ctypes.c_void_p(ptr), DTYPE_ID[dtype], n, first, ctypes.byref(cs),
+                                         ctypes.c_void_p(stream))
+    if rc:
+        raise RuntimeError(f"synth_fill_device failed ({rc})")
+
+
+def widen(arr: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact float64 value of stored gradients, by library conversions (for checks, not for the oracle)."""
+    if dtype == "f32":
+        return arr.astype(np.float64)
+    if dtype == "f16":
+        return arr.view(np.float16).astype(np.float64)
+    if dtype == "bf16":
+        return (arr.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    raise ValueError(dtype)

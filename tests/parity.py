@@ -1,0 +1,168 @@
+"""Shared machinery of the GPU parity tests: run a synthetic workload through libadama (via the
+simulated-backward harness) and through the fp64 oracle on the same seeded inputs, and compare.
+
+Tolerance (stated by the benchmark spec: max elementwise relative error 1e-5 with a 1e-6 absolute floor on
+theta, m and v for fp32 state), read as
+    |gpu - ref| <= max(1e-5 * |ref|, 1e-6)                                   (binding criterion)
+and, because m and v are far below 1e-6-relevant magnitudes at the configured gradient scales, the
+scale-aware criteria derived from the arithmetic are gated as well:
+    v      : |gpu - ref| <= 1e-5 * ref wherever ref > 0, and gpu == 0 exactly where ref == 0
+             (all terms are non-negative: error <= (N+2) * 2^-24 per mini-batch)
+    m      : |gpu - ref| <= 1e-5 * max(|ref|, rms(ref)) with the rms over the compared elements of the
+             tensor (m is a signed sum: cancellation can leave |m| far below the terms that formed it,
+             so the tensor's own scale replaces the fixed 1e-6 floor)
+    dtheta : the same bound on the parameter change of the step
+"""
+from __future__ import annotations
+
+import numpy as np
+
+import oracle
+import synth
+from synth import configs
+
+RTOL, ATOL = 1e-5, 1e-6
+SLICE = 4096
+
+
+def check_close(name: str, kind: str, gpu: np.ndarray, ref: np.ndarray, prev_gpu=None, prev_ref=None) -> dict:
+    gpu64 = gpu.astype(np.float64)
+    err = np.abs(gpu64 - ref)
+    assert np.all(np.isfinite(gpu64)), f"{name} {kind}: non-finite GPU values"
+    bound = np.maximum(RTOL * np.abs(ref), ATOL)
+    worst = int(np.argmax(err - bound))
+    assert np.all(err <= bound), (f"{name} {kind}: |gpu-ref| = {err[worst]:.3e} at {worst} "
+                                  f"(gpu {gpu64[worst]!r}, ref {ref[worst]!r})")
+    stats = {"max_abs": float(err.max(initial=0.0))}
+    if kind == "v":
+        pos = ref > 0
+        assert np.all(gpu64[~pos] == 0.0), f"{name} v: must be exactly 0 where the oracle's is"
+        assert np.all(gpu64 >= 0.0), f"{name} v: negative"
+        if pos.any():
+            rel = err[pos] / ref[pos]
+            assert rel.max() <= RTOL, f"{name} v: relative error {rel.max():.3e}"
+            stats["max_rel"] = float(rel.max())
+    elif kind == "m":
+        rms = float(np.sqrt(np.mean(ref ** 2))) if ref.size else 0.0
+        if rms > 0:
+            ratio = err / (RTOL * np.maximum(np.abs(ref), rms))
+            assert ratio.max() <= 1.0, f"{name} m: err/(1e-5*max(|ref|, rms)) = {ratio.max():.3f} (rms {rms:.3e})"
+            stats["max_over_scale"] = float(ratio.max() * RTOL)
+    elif kind == "theta" and prev_gpu is not None:
+        d_gpu = gpu64 - prev_gpu.astype(np.float64)
+        d_ref = ref - prev_ref
+        rms = float(np.sqrt(np.mean(d_ref ** 2))) if d_ref.size else 0.0
+        if rms > 0:
+            ratio = np.abs(d_gpu - d_ref) / (RTOL * np.maximum(np.abs(d_ref), rms))
+            assert ratio.max() <= 1.0, f"{name} dtheta: err/(1e-5*max(|ref|, rms)) = {ratio.max():.3f} (rms {rms:.3e})"
+            stats["dtheta_over_scale"] = float(ratio.max() * RTOL)
+    return stats
+
+
+def slices_of(n: int, rng: np.random.Generator, full_below: int = 65536, blocks: int = 4) -> list:
+    """Element ranges compared for a tensor of n elements: everything if small, else the first and last
+    SLICE elements plus `blocks` random SLICE-element blocks (starts deliberately not aligned)."""
+    if n <= full_below:
+        return [(0, n)]
+    out = [(0, SLICE), (n - SLICE, n)]
+    for _ in range(blocks):
+        s = int(rng.integers(SLICE, n - 2 * SLICE))
+        out.append((s, s + SLICE))
+    return sorted(out)
+
+
+class WorkloadRun:
+    """One workload on the GPU (harness) and in the oracle (on all elements or on sampled slices)."""
+
+    def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0"):
+        from paper_2305_19982_amd.harness import SimulatedBackward
+
+        self.w = w
+        self.sampled = sampled
+        self.hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, device=device, pack=pack)
+        rng = np.random.default_rng(1234)
+        self.slices = [slices_of(t.n, rng) if sampled else [(0, t.n)] for t in w.tensors]
+        # theta0: the device writes it, the host regenerates the same bits for the oracle
+        theta0 = []
+        for t in w.tensors:
+            synth.fill_device(self.hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, self.hb.stream_handle)
+            for (a, b) in self.slices[t.index]:
+                theta0.append(synth.fill_host(w.theta_spec(t.index), "f32", b - a, first=a))
+        self.key = [(t.index, a, b) for t in w.tensors for (a, b) in self.slices[t.index]]
+        self.ref = oracle.OracleState(theta0)
+        self.rows = {}
+        for r, (ti, a, b) in enumerate(self.key):
+            self.rows.setdefault(ti, []).append((r, a, b))
+        self.prev_gpu_theta = [self.download("theta", r) for r in range(len(self.key))]
+        for r in range(len(self.key)):
+            assert np.array_equal(self.prev_gpu_theta[r].astype(np.float64), self.ref.theta[r]), \
+                "device and host generators disagree on theta0"
+
+    def download(self, which: str, r: int) -> np.ndarray:
+        ti, a, b = self.key[r]
+        self.hb.synchronize()
+        return self.hb.tensor_view(which, ti)[a:b].cpu().numpy()
+
+    def produce(self, step: int, micro: int, li: int) -> None:
+        w = self.w
+        for ti in w.layers[li]:
+            synth.fill_device(self.hb.grad_ptr(ti), w.grad_spec(step, micro, ti), w.gdtype, w.tensors[ti].n,
+                              self.hb.stream_handle)
+
+    def oracle_fold_layer(self, step: int, micro: int, li: int) -> None:
+        w = self.w
+        gd = None if w.gdtype == "f32" else w.gdtype
+        for ti in w.layers[li]:
+            spec = w.grad_spec(step, micro, ti)
+            for (r, a, b) in self.rows[ti]:
+                g = synth.fill_host(spec, w.gdtype, b - a, first=a)
+                self.ref.fold(r, g, w.N, w.beta1, w.beta2, gdtype=gd)
+
+    def run_step(self, step: int, check_grad_bits: bool = False) -> dict:
+        w = self.w
+        self.hb.begin_step(w.beta1, w.beta2)
+        self.ref.begin_step(w.beta1, w.beta2)
+        for i in range(w.N):
+            for li in w.backward_layers():
+                self.produce(step, i, li)
+                if check_grad_bits:
+                    self.assert_grad_bits(step, i, li)
+                self.hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                self.oracle_fold_layer(step, i, li)
+        self.hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+        self.ref.apply(w.lr, w.eps, w.beta1, w.beta2)
+        assert self.hb.t == self.ref.t == step
+        return self.compare()
+
+    def assert_grad_bits(self, step: int, micro: int, li: int) -> None:
+        """What the device wrote into the gradient buffer is what the host regenerates for the oracle."""
+        import torch
+
+        w = self.w
+        self.hb.synchronize()
+        for ti in w.layers[li]:
+            n = w.tensors[ti].n
+            off = self.hb.grad_offset[ti] * self.hb.gbytes
+            raw = self.hb.grad_buffer[off: off + n * self.hb.gbytes].cpu().numpy()
+            dev = raw.view(np.float32 if w.gdtype == "f32" else np.uint16)
+            host = synth.fill_host(w.grad_spec(step, micro, ti), w.gdtype, n)
+            assert np.array_equal(dev, host), f"gradient bits differ for tensor {ti}"
+        del torch
+
+    def compare(self) -> dict:
+        worst = {}
+        for r, (ti, a, b) in enumerate(self.key):
+            name = f"{self.w.name}:{self.w.tensors[ti].name}[{a}:{b}]"
+            th = self.download("theta", r)
+            for kind, gpu, ref in (("m", self.download("m", r), self.ref.m[r]),
+                                   ("v", self.download("v", r), self.ref.v[r])):
+                for k, val in check_close(name, kind, gpu, ref).items():
+                    worst[f"{kind}.{k}"] = max(worst.get(f"{kind}.{k}", 0.0), val)
+            prev_ref = getattr(self, "_prev_ref_theta", None)
+            st = check_close(name, "theta", th, self.ref.theta[r], self.prev_gpu_theta[r],
+                             prev_ref[r] if prev_ref is not None else self.prev_gpu_theta[r].astype(np.float64))
+            for k, val in st.items():
+                worst[f"theta.{k}"] = max(worst.get(f"theta.{k}", 0.0), val)
+            self.prev_gpu_theta[r] = th
+        self._prev_ref_theta = [x.copy() for x in self.ref.theta]
+        return worst

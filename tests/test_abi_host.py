@@ -1,0 +1,202 @@
+"""Host-side logic of libadama that needs no GPU: the library loads, exports every symbol the
+header declares, rejects bad arguments before touching the device, treats empty inputs as no-ops,
+and its launch geometry covers every element of every tensor exactly once with in-bounds,
+aligned accesses."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2305_19982_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = 0x7F0000000000          # a device-looking address; never dereferenced on these paths
+
+
+@pytest.fixture(scope="module")
+def lib():
+    return binding.load()
+
+
+def test_header_symbols_are_exported(lib):
+    text = open(os.path.join(ROOT, "include", "adama.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = set(re.findall(r"\b(adama_[a-z_]+)\s*\(", text))
+    assert {"adama_begin_step", "adama_fold", "adama_fold_multi", "adama_apply", "adama_last_error"} <= names
+    for name in sorted(names):
+        assert hasattr(lib, name), f"{name} declared in include/adama.h but not exported"
+
+
+def test_header_constants_match_library(lib):
+    text = open(os.path.join(ROOT, "include", "adama.h")).read()
+    declared = int(re.search(r"#define ADAMA_MAX_TENSORS_PER_LAUNCH (\d+)", text).group(1))
+    assert binding.adama_max_tensors_per_launch() == declared
+
+
+def test_empty_inputs_are_noops(lib):
+    binding.adama_begin_step(None, None, 0, 0.9, 0.999)
+    binding.adama_fold(None, None, None, "bf16", 0, 4, 0.9, 0.999)
+    binding.adama_fold_multi([], 0, "f16", 4, 0.9, 0.999)
+    binding.adama_fold_multi([(None, None, None, 0), (None, None, None, 0)], None, "f32", 1, 0.9, 0.999)
+    binding.adama_apply(None, None, None, 0, 1e-3, 1e-8, 0.9, 0.999, 1)
+    binding.adama_apply_multi([], 0, 1e-3, 1e-8, 0.9, 0.999, 1)
+    binding.adama_begin_step_multi([], 0, 0.9, 0.999)
+
+
+BAD_FOLD = [
+    (dict(m=None), binding.ERR_INVALID_ARG, "m is NULL"),
+    (dict(v=None), binding.ERR_INVALID_ARG, "v is NULL"),
+    (dict(grad=None), binding.ERR_INVALID_ARG, "grad is NULL"),
+    (dict(N=0), binding.ERR_INVALID_ARG, "micro-batches"),
+    (dict(N=-3), binding.ERR_INVALID_ARG, "micro-batches"),
+    (dict(beta1=1.0), binding.ERR_INVALID_ARG, "[0, 1)"),
+    (dict(beta2=-0.1), binding.ERR_INVALID_ARG, "[0, 1)"),
+    (dict(beta2=float("nan")), binding.ERR_INVALID_ARG, "[0, 1)"),
+    (dict(gdt=7), binding.ERR_UNSUPPORTED_DTYPE, "dtype"),
+    (dict(m=FAKE + 2), binding.ERR_INVALID_ARG, "not aligned"),
+    (dict(grad=FAKE + 1, gdt=binding.BF16), binding.ERR_INVALID_ARG, "not aligned"),
+    (dict(grad=FAKE + 2, gdt=binding.F32), binding.ERR_INVALID_ARG, "not aligned"),
+    (dict(n=(1 << 40) + 1), binding.ERR_TOO_LARGE, "ADAMA_MAX_ELEMS"),
+]
+
+
+@pytest.mark.parametrize("override,status,text", BAD_FOLD, ids=[str(b[0]) for b in BAD_FOLD])
+def test_fold_rejects_bad_arguments(lib, override, status, text):
+    args = dict(m=FAKE, v=FAKE + (1 << 30), grad=FAKE + (2 << 30), gdt=binding.BF16, n=1000, N=4, beta1=0.9,
+                beta2=0.999)
+    args.update(override)
+    with pytest.raises(binding.AdamaError) as ei:
+        binding.adama_fold(args["m"], args["v"], args["grad"], args["gdt"], args["n"], args["N"], args["beta1"],
+                           args["beta2"])
+    assert ei.value.status == status
+    assert text in ei.value.message
+    assert text in binding.adama_last_error()
+    with pytest.raises(binding.AdamaError) as ei2:
+        binding.adama_fold_multi([(FAKE, FAKE + 4096, FAKE + 8192, 16), (args["m"], args["v"], args["grad"], args["n"])],
+                                 None, args["gdt"], args["N"], args["beta1"], args["beta2"])
+    assert ei2.value.status == status
+    if "NULL" in text or "aligned" in text or "MAX_ELEMS" in text:
+        assert "tensor 1" in ei2.value.message
+
+
+def test_fold_multi_rejects_null_list_and_negative_count(lib):
+    st = lib.adama_fold_multi(None, 3, binding.F32, 1, 0.9, 0.999, None)
+    assert st == binding.ERR_INVALID_ARG and "list is NULL" in binding.adama_last_error()
+    lst = binding.tensor_list([(FAKE, FAKE, FAKE, 4)])
+    st = lib.adama_fold_multi(lst, -1, binding.F32, 1, 0.9, 0.999, None)
+    assert st == binding.ERR_INVALID_ARG and "negative" in binding.adama_last_error()
+
+
+BAD_APPLY = [
+    (dict(t=0), "t >= 1"),
+    (dict(t=-5), "t >= 1"),
+    (dict(theta=None), "theta is NULL"),
+    (dict(m=None), "m is NULL"),
+    (dict(lr=float("inf")), "lr"),
+    (dict(eps=-1e-8), "eps"),
+    (dict(eps=float("nan")), "eps"),
+    (dict(beta1=1.0), "[0, 1)"),
+    (dict(beta2=1.5), "[0, 1)"),
+]
+
+
+@pytest.mark.parametrize("override,text", BAD_APPLY, ids=[str(b[0]) for b in BAD_APPLY])
+def test_apply_rejects_bad_arguments(lib, override, text):
+    args = dict(theta=FAKE, m=FAKE + (1 << 30), v=FAKE + (2 << 30), n=100, lr=1e-3, eps=1e-8, beta1=0.9, beta2=0.999, t=1)
+    args.update(override)
+    with pytest.raises(binding.AdamaError) as ei:
+        binding.adama_apply(args["theta"], args["m"], args["v"], args["n"], args["lr"], args["eps"], args["beta1"],
+                            args["beta2"], args["t"])
+    assert ei.value.status == binding.ERR_INVALID_ARG and text in ei.value.message
+
+
+def test_begin_step_hyper_parameters(lib):
+    with pytest.raises(binding.AdamaError):
+        binding.adama_begin_step(FAKE, FAKE + 4096, 10, -0.5, 0.999)
+    with pytest.raises(binding.AdamaError):
+        binding.adama_begin_step(FAKE, FAKE + 4096, 10, 0.9, float("inf"))
+    with pytest.raises(binding.AdamaError):
+        binding.adama_begin_step(FAKE, None, 10, 0.9, 0.999)
+    # beta2 above 1 is legal here (data-parallel decay by M*beta2) -- with n == 0 nothing is launched
+    binding.adama_begin_step(None, None, 0, 0.9, 8 * 0.999)
+
+
+# ---------------------------------------------------------------------------
+# launch geometry
+# ---------------------------------------------------------------------------
+def _walk_and_check(entries, op, gdt):
+    touched, nvec, nsc, launches = binding.adama_debug_walk(entries, op, gdt)
+    for k, (tch, e) in enumerate(zip(touched, entries)):
+        arr = np.frombuffer(tch, dtype=np.uint8)
+        assert arr.size == e[3]
+        assert np.all(arr == 1), f"tensor {k}: elements touched {np.unique(arr)} times"
+    assert nvec * 4 + nsc == sum(e[3] for e in entries)
+    return nvec, nsc, launches
+
+
+@pytest.mark.parametrize("gdt,gb", [("f32", 4), ("bf16", 2), ("f16", 2)])
+def test_geometry_aligned_tensors_use_vector_accesses(lib, gdt, gb):
+    rng = np.random.default_rng(1)
+    sizes = [0, 1, 3, 4, 5, 1023, 1024, 1025, 4095, 4096, 4097, 12345, 65536, 0, 100001]
+    entries = []
+    a = FAKE
+    for n in sizes:
+        entries.append((a, a + (1 << 32), a + (2 << 32), n))
+        a += (4 * n + 255) // 256 * 256
+    nvec, nsc, launches = _walk_and_check(entries, 1, gdt)
+    assert launches == 1
+    assert nsc == sum(n % 4 for n in sizes)          # only the ragged tails go element by element
+    del rng
+
+
+@pytest.mark.parametrize("op,gdt,gb", [(0, "f32", 4), (1, "f32", 4), (1, "bf16", 2), (1, "f16", 2), (2, "f32", 4)])
+def test_geometry_misaligned_and_large(lib, op, gdt, gb):
+    rng = np.random.default_rng(2)
+    entries = []
+    for i in range(40):
+        n = int(rng.integers(1, 30000))
+        pre = int(rng.integers(0, 4))
+        co = bool(rng.integers(0, 2))
+        a = FAKE + (i << 24) + 4 * pre
+        b = FAKE + (1 << 36) + (i << 24) + 4 * (pre if co else (pre + 1) % 4)
+        c = FAKE + (2 << 36) + (i << 24) + gb * pre
+        entries.append((a, b, c, n))
+    # one launch big enough for the 4096-element chunks, with every misalignment
+    for pre in range(4):
+        n = (1 << 22) + 3 * pre + 1
+        entries.append((FAKE + (3 << 36) + (pre << 28) + 4 * pre, FAKE + (4 << 36) + (pre << 28) + 4 * pre,
+                        FAKE + (5 << 36) + (pre << 28) + gb * pre, n))
+    nvec, nsc, launches = _walk_and_check(entries, op, gdt)
+    assert launches == 1 and nvec > 0 and nsc > 0
+
+
+def test_geometry_many_tensors_split_into_launches(lib):
+    cap = binding.adama_max_tensors_per_launch()
+    rng = np.random.default_rng(3)
+    entries = []
+    a = FAKE
+    for i in range(2 * cap + 17):
+        n = int(rng.integers(0, 3000))
+        entries.append((a, a + (1 << 32), a + (2 << 32), n))
+        a += 4 * n                                   # packed back to back: all misalignments occur
+    nvec, nsc, launches = _walk_and_check(entries, 1, "bf16")
+    assert launches == 3
+
+
+def test_geometry_walk_flags_nothing_on_workload_shapes(lib):
+    """The tensor lists of the reduced benchmark workloads, as the harness lays them out (tight packing)."""
+    from synth import configs
+
+    for name in ("c1", "c3", "c4"):
+        w = configs.reduced(name)
+        off = 0
+        for idx in w.layers:
+            entries, goff = [], 0
+            for ti in idx:
+                n = w.tensors[ti].n
+                entries.append((FAKE + 4 * off, FAKE + (1 << 36) + 4 * off, FAKE + (2 << 36) + w.grad_bytes * goff, n))
+                off += n
+                goff += n
+            _walk_and_check(entries, 1, w.gdtype)

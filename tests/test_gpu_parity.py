@@ -1,0 +1,255 @@
+"""GPU parity: libadama (through its C ABI) against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+
+import oracle
+import synth
+from parity import WorkloadRun, check_close
+from synth import configs
+
+pytestmark = pytest.mark.gpu
+
+B1, B2, LR, EPS = 0.9, 0.999, 1e-3, 1e-8
+
+
+@pytest.fixture(scope="module")
+def torch_cuda():
+    import torch
+
+    assert torch.cuda.is_available()
+    from paper_2305_19982_amd import binding
+
+    binding.load()
+    return torch
+
+
+def _log(msg):
+    print(msg, flush=True)
+
+
+# ---------------------------------------------------------------------------
+# the synthetic-input generator writes the same bits on the device and on the host
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "f16"])
+def test_device_and_host_generators_agree(torch_cuda, dtype):
+    torch = torch_cuda
+    n = 3_000_001
+    spec = synth.Spec(key=synth.stream_key(7, 1, 2, 3), sigma=3e-3, p_zero=0.01, p_outlier=0.002, p_sub=0.01)
+    buf = torch.empty(n * 4, dtype=torch.uint8, device="cuda:0")
+    synth.fill_device(buf.data_ptr(), spec, dtype, n, 0, first=12345)
+    torch.cuda.synchronize()
+    nbytes = n * synth.gen.DTYPE_BYTES[dtype]
+    dev = buf[:nbytes].cpu().numpy().view(np.float32 if dtype == "f32" else np.uint16)
+    host = synth.fill_host(spec, dtype, n, first=12345)
+    assert np.array_equal(dev, host)
+
+
+# ---------------------------------------------------------------------------
+# single calls on awkward shapes: lengths around chunk boundaries, misaligned starts
+# ---------------------------------------------------------------------------
+LENGTHS = [1, 2, 3, 4, 5, 7, 63, 64, 255, 1023, 1024, 1025, 4095, 4096, 4097, 8191, 12289, 1 << 16,
+           (1 << 22) + 5, (1 << 22) + 4096 * 3 + 1]
+
+
+def _fold_case(torch, gdt, n, pre_state, pre_grad, N, kind="fold"):
+    """One begin_step + fold(s) + apply on a tensor placed `pre` elements past an aligned address."""
+    from paper_2305_19982_amd import binding
+
+    gbytes = synth.gen.DTYPE_BYTES[gdt]
+    pad = 64
+    theta = torch.zeros(n + pad, dtype=torch.float32, device="cuda:0")
+    m = torch.zeros(n + pad, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n + pad, dtype=torch.float32, device="cuda:0")
+    g = torch.zeros((n + pad) * gbytes, dtype=torch.uint8, device="cuda:0")
+    key = synth.stream_key(11, n, pre_state, pre_grad, N)
+    th0 = synth.fill_host(synth.Spec(key=key, sigma=0.02), "f32", n)
+    m0 = synth.fill_host(synth.Spec(key=key + 1, sigma=1e-3), "f32", n)
+    v0 = np.abs(synth.fill_host(synth.Spec(key=key + 2, sigma=1e-5), "f32", n))
+    sl = slice(pre_state, pre_state + n)
+    theta[sl] = torch.from_numpy(th0).cuda()
+    m[sl] = torch.from_numpy(m0).cuda()
+    v[sl] = torch.from_numpy(v0).cuda()
+    p_t, p_m, p_v = (x.data_ptr() + 4 * pre_state for x in (theta, m, v))
+    p_g = g.data_ptr() + gbytes * pre_grad
+    ref = oracle.OracleState([th0])
+    ref.m[0][:] = m0
+    ref.v[0][:] = v0
+    ref.t = 2
+    binding.adama_begin_step(p_m, p_v, n, B1, B2)
+    ref.begin_step(B1, B2)
+    gd = None if gdt == "f32" else gdt
+    for i in range(N):
+        spec = synth.Spec(key=key + 10 + i, sigma=1e-2, p_zero=0.02, p_sub=0.02 if gdt == "f16" else 0.0,
+                          p_outlier=0.001)
+        synth.fill_device(p_g, spec, gdt, n, 0)
+        binding.adama_fold(p_m, p_v, p_g, gdt, n, N, B1, B2)
+        ref.fold(0, synth.fill_host(spec, gdt, n), N, B1, B2, gdtype=gd)
+    binding.adama_apply(p_t, p_m, p_v, n, LR, EPS, B1, B2, ref.t)
+    ref.apply(LR, EPS, B1, B2)
+    torch.cuda.synchronize()
+    name = f"{gdt} n={n} pre={pre_state}/{pre_grad} N={N}"
+    check_close(name, "m", m[sl].cpu().numpy(), ref.m[0])
+    check_close(name, "v", v[sl].cpu().numpy(), ref.v[0])
+    check_close(name, "theta", theta[sl].cpu().numpy(), ref.theta[0], th0, th0.astype(np.float64))
+    # nothing outside the tensor was written
+    for arr in (theta, m, v):
+        assert float(arr[:pre_state].abs().sum()) == 0.0 and float(arr[pre_state + n:].abs().sum()) == 0.0, name
+
+
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+def test_fold_lengths_aligned(torch_cuda, gdt):
+    for n in LENGTHS:
+        _log(f"case {gdt} n={n} aligned")
+        _fold_case(torch_cuda, gdt, n, 0, 0, N=3)
+
+
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+def test_fold_misaligned_starts(torch_cuda, gdt):
+    for n in (1, 6, 1021, 4099, 70001, (1 << 22) + 11):
+        for pre_state, pre_grad in ((1, 1), (2, 2), (3, 3), (1, 0), (0, 3), (2, 5), (3, 7)):
+            _log(f"case {gdt} n={n} pre={pre_state}/{pre_grad}")
+            _fold_case(torch_cuda, gdt, n, pre_state, pre_grad, N=2)
+
+
+def test_fold_n1_and_large_N(torch_cuda):
+    _fold_case(torch_cuda, "bf16", 50001, 0, 0, N=1)
+    _fold_case(torch_cuda, "f16", 50001, 0, 0, N=64)
+
+
+def test_fp16_every_finite_pattern_including_subnormals(torch_cuda):
+    """All 63488 finite fp16 patterns through one fold: widening happens before scaling and squaring."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    bits = bits[np.isfinite(bits.view(np.float16))]
+    n = bits.size
+    g = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    N = 4
+    binding.adama_fold(m, v, g, "f16", n, N, B1, B2)
+    torch.cuda.synchronize()
+    rm, rv = np.zeros(n), np.zeros(n)
+    oracle.fold(rm, rv, bits, N, B1, B2, gdtype="f16")
+    gm, gv = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
+    nz = rm != 0
+    assert np.all(gm[~nz] == 0) and np.all(gv[~nz] == 0)
+    assert np.max(np.abs(gm[nz] - rm[nz]) / np.abs(rm[nz])) <= 2.0 ** -22
+    assert np.max(np.abs(gv[nz] - rv[nz]) / rv[nz]) <= 2.0 ** -22
+    assert np.all(gv[nz] > 0), "a non-zero fp16 gradient (subnormals included) must leave v > 0"
+
+
+def test_bf16_pattern_sweep(torch_cuda):
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    val = (bits.astype(np.uint32) << 16).view(np.float32)
+    keep = np.isfinite(val) & (np.abs(val) < 1e15) & ((np.abs(val) > 1e-15) | (val == 0))
+    bits = bits[keep]
+    n = bits.size
+    g = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    binding.adama_fold(m, v, g, "bf16", n, 2, B1, B2)
+    torch.cuda.synchronize()
+    rm, rv = np.zeros(n), np.zeros(n)
+    oracle.fold(rm, rv, bits, 2, B1, B2, gdtype="bf16")
+    gm, gv = m.cpu().numpy().astype(np.float64), v.cpu().numpy().astype(np.float64)
+    nz = rm != 0
+    assert np.all(gm[~nz] == 0) and np.all(gv[~nz] == 0)
+    assert np.max(np.abs(gm[nz] - rm[nz]) / np.abs(rm[nz])) <= 2.0 ** -22
+    assert np.max(np.abs(gv[nz] - rv[nz]) / rv[nz]) <= 2.0 ** -22
+
+
+# ---------------------------------------------------------------------------
+# fold_multi == repeated fold, bit for bit; lists longer than one launch's table
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+def test_fold_multi_bitwise_equals_fold(torch_cuda, gdt):
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    rng = np.random.default_rng(5)
+    cap = binding.adama_max_tensors_per_launch()
+    sizes = [int(x) for x in rng.integers(0, 9000, 2 * cap + 9)] + [300001, (1 << 22) + 77, 0, 1]
+    gbytes = synth.gen.DTYPE_BYTES[gdt]
+    total = sum(sizes)
+    arena = {k: torch.zeros(total + 8, dtype=torch.float32, device="cuda:0") for k in ("m1", "v1", "m2", "v2")}
+    g = torch.zeros((total + 8) * gbytes, dtype=torch.uint8, device="cuda:0")
+    synth.fill_device(g.data_ptr(), synth.Spec(key=99, sigma=1e-2, p_zero=0.01), gdt, total, 0)
+    for k in ("m1", "m2"):
+        synth.fill_device(arena[k].data_ptr(), synth.Spec(key=5, sigma=1e-3), "f32", total, 0)
+    for k in ("v1", "v2"):
+        synth.fill_device(arena[k].data_ptr(), synth.Spec(key=6, sigma=1e-4), "f32", total, 0)
+        arena[k].abs_()
+    entries1, entries2, off = [], [], 0
+    for n in sizes:                      # packed back to back: every misalignment occurs
+        entries1.append((arena["m1"].data_ptr() + 4 * off, arena["v1"].data_ptr() + 4 * off, g.data_ptr() + gbytes * off, n))
+        entries2.append((arena["m2"].data_ptr() + 4 * off, arena["v2"].data_ptr() + 4 * off, g.data_ptr() + gbytes * off, n))
+        off += n
+    binding.adama_fold_multi(entries1, None, gdt, 4, B1, B2)
+    for (pm, pv, pg, n) in entries2:
+        binding.adama_fold(pm, pv, pg, gdt, n, 4, B1, B2)
+    torch.cuda.synchronize()
+    assert torch.equal(arena["m1"], arena["m2"]) and torch.equal(arena["v1"], arena["v2"])
+    assert float(arena["m1"][total:].abs().sum()) == 0.0
+
+
+def test_state_multi_bitwise_equals_single(torch_cuda):
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    rng = np.random.default_rng(6)
+    sizes = [int(x) for x in rng.integers(0, 5000, 150)] + [(1 << 22) + 3]
+    total = sum(sizes)
+    a = {k: torch.zeros(total, dtype=torch.float32, device="cuda:0") for k in ("t1", "m1", "v1", "t2", "m2", "v2")}
+    for s, (kt, km, kv) in enumerate((("t1", "m1", "v1"), ("t2", "m2", "v2"))):
+        synth.fill_device(a[kt].data_ptr(), synth.Spec(key=1, sigma=0.02), "f32", total, 0)
+        synth.fill_device(a[km].data_ptr(), synth.Spec(key=2, sigma=1e-3), "f32", total, 0)
+        synth.fill_device(a[kv].data_ptr(), synth.Spec(key=3, sigma=1e-5), "f32", total, 0)
+        a[kv].abs_()
+    l1, l2, off = [], [], 0
+    for n in sizes:
+        l1.append((a["t1"].data_ptr() + 4 * off, a["m1"].data_ptr() + 4 * off, a["v1"].data_ptr() + 4 * off, n))
+        l2.append((a["t2"].data_ptr() + 4 * off, a["m2"].data_ptr() + 4 * off, a["v2"].data_ptr() + 4 * off, n))
+        off += n
+    binding.adama_begin_step_multi(l1, None, B1, B2)
+    binding.adama_apply_multi(l1, None, LR, EPS, B1, B2, 3)
+    for (pt, pm, pv, n) in l2:
+        binding.adama_begin_step(pm, pv, n, B1, B2)
+    for (pt, pm, pv, n) in l2:
+        binding.adama_apply(pt, pm, pv, n, LR, EPS, B1, B2, 3)
+    torch.cuda.synchronize()
+    for k in ("t", "m", "v"):
+        assert torch.equal(a[k + "1"], a[k + "2"]), k
+
+
+def test_begin_step_accepts_ddp_decay(torch_cuda):
+    """Sec. 3.3: devices decay v by M*beta2 (> 1 allowed)."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n = 10007
+    m = torch.full((n,), 0.5, dtype=torch.float32, device="cuda:0")
+    v = torch.full((n,), 0.25, dtype=torch.float32, device="cuda:0")
+    binding.adama_begin_step(m, v, n, 0.9, 8 * 0.999)
+    torch.cuda.synchronize()
+    assert np.allclose(m.cpu().numpy(), np.float32(0.9) * np.float32(0.5), rtol=0, atol=0)
+    assert np.allclose(v.cpu().numpy(), np.float32(8 * 0.999) * np.float32(0.25), rtol=0, atol=0)
+
+
+# ---------------------------------------------------------------------------
+# the five workloads at reduced size: every element, every step
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("pack", ["aligned", "tight"])
+def test_reduced_workload_full_parity(torch_cuda, name, pack):
+    w = configs.reduced(name)
+    run = WorkloadRun(w, pack=pack, sampled=False)
+    for step in range(1, w.steps + 1):
+        stats = run.run_step(step, check_grad_bits=(step == 1 and pack == "aligned"))
+        _log(f"{w.name} [{pack}] step {step}: {stats}")
+    assert run.hb.peak_grad_bytes <= (w.largest_layer_elems + 128 * 32) * w.grad_bytes
+    assert run.hb.peak_grad_bytes < run.hb.whole_model_grad_bytes
