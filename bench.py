@@ -99,8 +99,8 @@ def main() -> int:
         synth.fill_device(hb.grad_ptr(t.index), w.grad_spec(1, 0, t.index), w.gdtype, t.n, sh)
     hb.synchronize()
 
-    # the fold launches of the dominant kernel (big-chunk variant): layers of at least 2^22 elements
-    big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= (1 << 22)}
+    # the fold launches of the dominant kernel (big-chunk variant): layers of at least 2^20 elements
+    big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= (1 << 20)}
     fold_events = []
 
     def one_step(timed: bool) -> None:
@@ -162,7 +162,7 @@ def main() -> int:
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U=4>",
+                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U=2,nt>",
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},
