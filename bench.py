@@ -72,6 +72,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB copy kernel (the known-size reference for hardware traffic counters)")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -99,24 +101,44 @@ def main() -> int:
         synth.fill_device(hb.grad_ptr(t.index), w.grad_spec(1, 0, t.index), w.gdtype, t.n, sh)
     hb.synchronize()
 
-    # the fold launches of the dominant kernel (big-chunk variant): layers of at least 2^20 elements
-    big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= (1 << 20)}
+    # the fold launches of the dominant kernel: layers long enough for the big-chunk instantiation
+    tune = binding.adama_tuning()
+    big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= tune["big_launch_elems"]}
     fold_events = []
 
     def one_step(timed: bool) -> None:
+        """timed: bracket every run of consecutive dominant-kernel launches with one HIP event pair
+        recorded on the launch stream (a pair per launch would add its own overhead to each)."""
         hb.begin_step(w.beta1, w.beta2)
         for _ in range(w.N):
+            run_start, run_elems, run_launches = None, 0, 0
             for li in w.backward_layers():
-                if timed and li in big_layers:
-                    e0 = torch.cuda.Event(enable_timing=True)
-                    e1 = torch.cuda.Event(enable_timing=True)
-                    e0.record(hb.stream)
-                    hb.fold_layer(li, w.N, w.beta1, w.beta2)
-                    e1.record(hb.stream)
-                    fold_events.append((e0, e1, w.layer_elems(li)))
-                else:
-                    hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                big = li in big_layers
+                if timed and big and run_start is None:
+                    run_start = torch.cuda.Event(enable_timing=True)
+                    run_start.record(hb.stream)
+                if timed and not big and run_start is not None:
+                    end = torch.cuda.Event(enable_timing=True)
+                    end.record(hb.stream)
+                    fold_events.append((run_start, end, run_elems, run_launches))
+                    run_start, run_elems, run_launches = None, 0, 0
+                hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                if big:
+                    run_elems += w.layer_elems(li)
+                    run_launches += 1
+            if timed and run_start is not None:
+                end = torch.cuda.Event(enable_timing=True)
+                end.record(hb.stream)
+                fold_events.append((run_start, end, run_elems, run_launches))
         hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+
+    if args.calibration_copy:
+        src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        torch.cuda.synchronize()
+        synth.gen.copy_device(dst.data_ptr(), src.data_ptr(), 1 << 30, sh)
+        hb.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         one_step(False)
@@ -134,9 +156,9 @@ def main() -> int:
     for _ in range(min(2, args.steps)):
         one_step(True)
     hb.synchronize()
-    fold_ms = sum(e0.elapsed_time(e1) for e0, e1, _ in fold_events)
-    fold_bytes = sum(n for _, _, n in fold_events) * (16 + w.grad_bytes)
-    launches = len(fold_events)
+    fold_ms = sum(e0.elapsed_time(e1) for e0, e1, _, _ in fold_events)
+    fold_bytes = sum(n for _, _, n, _ in fold_events) * (16 + w.grad_bytes)
+    launches = sum(k for _, _, _, k in fold_events)
     achieved = fold_bytes / (fold_ms * 1e-3) / 1e9 if fold_ms > 0 else 0.0
 
     step_bytes = algorithmic_bytes_per_step(w)
@@ -162,7 +184,7 @@ def main() -> int:
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U=2,nt>",
+                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U={tune['u_big']},policy={tune['policy_bits']}>",
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},

@@ -112,6 +112,12 @@ const char *adama_last_error(void);
 #define ADAMA_MAX_TENSORS_PER_LAUNCH 96
 int adama_max_tensors_per_launch(void);
 
+/* Host-only: the launch policy compiled into the library, for benchmark labels.  A launch whose
+ * tensors total at least *big_launch_elems elements uses chunks of 1024 * *u_big elements, shorter
+ * launches use 1024 * *u_small; *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal
+ * state loads, 4 = non-temporal stores, 8 = buffer-descriptor addressing.  Any pointer may be NULL. */
+void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits);
+
 /*
  * Host-only check of the launch geometry (no device needed, nothing is dereferenced): walks every
  * (launch, chunk, thread, access) the kernels would issue for `list` and adds 1 to touched[k][e]

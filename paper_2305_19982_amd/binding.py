@@ -71,6 +71,9 @@ def load() -> ctypes.CDLL:
     lib.adama_last_error.argtypes = []
     lib.adama_max_tensors_per_launch.restype = i32
     lib.adama_max_tensors_per_launch.argtypes = []
+    lib.adama_tuning.restype = None
+    lib.adama_tuning.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_ulonglong),
+                                 ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -94,6 +97,12 @@ def adama_last_error() -> str:
 
 def adama_max_tensors_per_launch() -> int:
     return int(load().adama_max_tensors_per_launch())
+
+
+def adama_tuning() -> dict:
+    us, ub, pol, big = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_ulonglong(0)
+    load().adama_tuning(ctypes.byref(us), ctypes.byref(ub), ctypes.byref(big), ctypes.byref(pol))
+    return {"u_small": us.value, "u_big": ub.value, "big_launch_elems": big.value, "policy_bits": pol.value}
 
 
 def tensor_list(entries) -> ctypes.Array:

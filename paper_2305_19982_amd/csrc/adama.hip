@@ -33,7 +33,7 @@ adama_status fail(adama_status st, const char *fmt, ...)
 
 // ---- tuning constants (measured on MI355X with a sweep over U, grid shape and cache policy) ----
 constexpr int kUSmall = 1;                    // chunk = 1024 elements: many workgroups for small launches
-constexpr int kUBig = 2;                      // chunk = 2048 elements: 4..6 16-byte loads in flight per thread
+constexpr int kUBig = 4;                      // chunk = 4096 elements: 8..12 16-byte loads in flight per thread
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
@@ -75,7 +75,9 @@ adama_status for_each_batch(const Desc *descs, int count, Emit &&emit)
             start += chunks_of(misalign_elems(b.tab.t[j].a), b.tab.t[j].n, chunk);
         }
         b.tab.chunk_start[k] = (uint32_t)start;
+        for (int j = k + 1; j < kMaxTensors + 17; ++j) b.tab.chunk_start[j] = 0xFFFFFFFFu;
         b.tab.count = (uint32_t)k;
+        b.tab.total = (uint32_t)start;
         b.total = (uint32_t)start;
         if (start >= (1ull << 31)) return fail(ADAMA_ERR_TOO_LARGE, "launch of %llu chunks", (unsigned long long)start);
         if (b.total > 0) {
@@ -208,6 +210,14 @@ extern "C" {
 const char *adama_last_error(void) { return g_error; }
 
 int adama_max_tensors_per_launch(void) { return kMaxTensors; }
+
+void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits)
+{
+    if (u_small) *u_small = kUSmall;
+    if (u_big) *u_big = kUBig;
+    if (big_launch_elems) *big_launch_elems = kBigLaunchElems;
+    if (policy_bits) *policy_bits = kNtPolicy;
+}
 
 adama_status adama_fold_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
                               double beta2, hipStream_t stream)

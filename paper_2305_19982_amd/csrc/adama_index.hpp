@@ -39,8 +39,11 @@ struct Desc {
 template <int MaxT>
 struct Table {
     Desc t[MaxT];
-    uint32_t chunk_start[MaxT + 1];   // chunk_start[k] = first chunk of tensor k; [count] = total
+    // chunk_start[k] = first chunk of tensor k; [count] = total; entries past [count] = 0xFFFFFFFF.
+    // Sized so that the 16-wide search blocks of find_tensor never read past the array.
+    uint32_t chunk_start[MaxT + 17];
     uint32_t count;
+    uint32_t total;                   // == chunk_start[count]
     uint32_t pad;
 };
 
@@ -65,15 +68,20 @@ ADAMA_HD uint64_t chunks_of(uint32_t pre, uint64_t n, uint32_t chunk)
 
 // Largest k in [0, count) with start[k] <= c, given start[0] == 0 <= c < start[count].
 // Zero-length tensors (start[k] == start[k+1]) are skipped by the tie rule.
+// start[] is non-decreasing, so k is the number of entries start[1..count-1] that are <= c.  Counting
+// them in blocks of 16 keeps every load independent of the others (one scalar-cache latency for the
+// whole search instead of one per bisection step); entries past `count` must hold 0xFFFFFFFF.
 template <typename StartArray>
 ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t count, uint32_t c)
 {
-    uint32_t lo = 0, hi = count;
-    while (hi - lo > 1) {
-        uint32_t mid = (lo + hi) >> 1;
-        if (start[mid] <= c) lo = mid; else hi = mid;
+    uint32_t k = 0;
+    for (uint32_t base = 0; base < count; base += 16) {
+#if defined(__HIPCC__)
+#pragma unroll
+#endif
+        for (uint32_t j = 0; j < 16; ++j) k += (start[base + j + 1] <= c) ? 1u : 0u;
     }
-    return lo;
+    return k;
 }
 
 // Chunk lc of a tensor covers coordinates [lc*chunk, (lc+1)*chunk).  It is "interior" when the

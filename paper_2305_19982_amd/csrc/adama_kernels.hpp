@@ -14,8 +14,8 @@
 // an interior chunk each thread issues all of its U 16-byte loads per array
 // before the first use, so a wavefront has 2U..3U independent 1-KiB requests
 // outstanding.  The table of tensors of the launch arrives in the kernel
-// argument block and is staged once per workgroup in LDS, together with the
-// per-tensor chunk prefix that maps a chunk number to its tensor.
+// argument block, together with the per-tensor chunk prefix that maps a chunk
+// number to its tensor; both are read through the scalar cache.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -41,8 +41,10 @@ __device__ __forceinline__ ADAMA_GLOBAL T *global_ptr(const void *p, uint64_t el
     return (ADAMA_GLOBAL T *)(reinterpret_cast<uintptr_t>(p) + elem_offset_bytes);
 }
 
-// Cache-policy bits of a kernel instantiation: which streams use non-temporal accesses.
-enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4 };
+// Policy bits of a kernel instantiation: which streams use non-temporal accesses, and whether interior
+// chunks address memory through buffer descriptors (scalar base + 32-bit lane offset) instead of
+// 64-bit per-lane global addresses.
+enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4, kBufferAddressing = 8 };
 
 // decay: s0 = beta1, s1 = beta2.  fold: s0 = (1-beta1)/N, s1 = (1-beta2)/N^2.
 // apply: s0 = lr/(1-beta1^t), s1 = 1/sqrt(1-beta2^t), s2 = eps.
@@ -62,6 +64,31 @@ __device__ __forceinline__ void st(ADAMA_GLOBAL T *p, T x)
 {
     if constexpr (NT) __builtin_nontemporal_store(x, p);
     else *p = x;
+}
+
+// Buffer-descriptor access to one chunk: base is wave-uniform, `bytes` bounds the range (the hardware
+// drops anything outside it), offsets are 32-bit.  aux bit 1 is the non-temporal hint on gfx950.
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void *base, uint64_t byte_offset, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(reinterpret_cast<uintptr_t>(base) + byte_offset),
+                                             0, bytes, 0x00020000);
+}
+
+template <bool NT, typename T>
+__device__ __forceinline__ T buf_ld(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset)
+{
+    constexpr int aux = NT ? 2 : 0;
+    if constexpr (sizeof(T) == 16) return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, aux));
+    else return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, byte_offset, 0, aux));
+}
+
+template <bool NT>
+__device__ __forceinline__ void buf_st(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset, f32x4 x)
+{
+    constexpr int aux = NT ? 2 : 0;
+    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x), r, byte_offset, 0, aux);
 }
 
 // ---- gradient storage formats: 4-element vector type, element type, exact widening to float32 ----
@@ -160,6 +187,64 @@ template <int OpK, int GT, int U, int NT>
 __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint32_t tid, const Scalars &sc)
 {
     constexpr bool ntg = (NT & kNtGradLoad) != 0, ntl = (NT & kNtStateLoad) != 0, nts = (NT & kNtStore) != 0;
+    if constexpr ((NT & kBufferAddressing) != 0) {
+        constexpr uint32_t chunk = kBlock * kGroup * U;
+        __amdgpu_buffer_rsrc_t ra = chunk_rsrc(d.a, e0 * 4, chunk * 4);
+        __amdgpu_buffer_rsrc_t rb = chunk_rsrc(d.b, e0 * 4, chunk * 4);
+        if constexpr (OpK == kFold) {
+            using G = Grad<GT>;
+            constexpr uint32_t gsz = sizeof(typename G::Vec);
+            __amdgpu_buffer_rsrc_t rc = chunk_rsrc(d.c, e0 * sizeof(typename G::Elem), chunk * sizeof(typename G::Elem));
+            typename G::Vec g[U];
+            f32x4 m[U], v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                g[u] = buf_ld<ntg, typename G::Vec>(rc, i * gsz);
+                m[u] = buf_ld<ntl, f32x4>(ra, i * 16);
+                v[u] = buf_ld<ntl, f32x4>(rb, i * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                fold4(m[u], v[u], G::widen(g[u]), sc);
+                buf_st<nts>(ra, i * 16, m[u]);
+                buf_st<nts>(rb, i * 16, v[u]);
+            }
+        } else if constexpr (OpK == kDecay) {
+            f32x4 m[U], v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                m[u] = buf_ld<ntl, f32x4>(ra, i * 16);
+                v[u] = buf_ld<ntl, f32x4>(rb, i * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                decay4(m[u], v[u], sc);
+                buf_st<nts>(ra, i * 16, m[u]);
+                buf_st<nts>(rb, i * 16, v[u]);
+            }
+        } else {
+            __amdgpu_buffer_rsrc_t rc = chunk_rsrc(d.c, e0 * 4, chunk * 4);
+            f32x4 th[U], m[U], v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                th[u] = buf_ld<ntl, f32x4>(ra, i * 16);
+                m[u] = buf_ld<ntl, f32x4>(rb, i * 16);
+                v[u] = buf_ld<ntl, f32x4>(rc, i * 16);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                uint32_t i = u * kBlock + tid;
+                apply4(th[u], m[u], v[u], sc);
+                buf_st<nts>(ra, i * 16, th[u]);
+            }
+        }
+        return;
+    }
     ADAMA_GLOBAL f32x4 *A = global_ptr<f32x4>(d.a, e0 * 4);
     ADAMA_GLOBAL f32x4 *B = global_ptr<f32x4>(d.b, e0 * 4);
     if constexpr (OpK == kFold) {
@@ -272,27 +357,24 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
 
 // OpK: Op.  GT: GradType (fold only).  U: 16-byte groups per thread per chunk (chunk = 1024*U elements).
 // NT: cache-policy bits.  Grid: any number of workgroups >= 1; workgroup w takes chunks w, w+grid, ...
+//
+// The tensor table stays in the kernel argument block and is read with scalar loads: the chunk number
+// depends on the workgroup id alone, so the search for its tensor and the fetch of the descriptor are
+// wave-uniform and are served by the scalar cache.  (Staging the table in LDS first was measured and
+// dropped: in a kernel that saturates the vector memory path, the vector loads that would fill LDS
+// queue behind the streaming traffic and delay every workgroup's first data load by microseconds.)
 template <int OpK, int GT, int U, int NT>
 __global__ void __launch_bounds__(kBlock) multi_tensor_kernel(const Table<kMaxTensors> tab, const Scalars sc)
 {
-    __shared__ Desc s_desc[kMaxTensors];
-    __shared__ uint32_t s_start[kMaxTensors + 1];
     const uint32_t tid = threadIdx.x;
     const uint32_t count = tab.count;
-    for (uint32_t i = tid; i < count; i += kBlock) s_desc[i] = tab.t[i];
-    for (uint32_t i = tid; i <= count; i += kBlock) s_start[i] = tab.chunk_start[i];
-    __syncthreads();
     constexpr uint32_t chunk = kBlock * kGroup * U;
     constexpr uint32_t c_bytes = OpK == kDecay ? 0u : (OpK == kApply || GT == kF32) ? 4u : 2u;
-    const uint32_t total = tab.chunk_start[count];
+    const uint32_t total = tab.total;
     for (uint32_t c = blockIdx.x; c < total; c += gridDim.x) {
-        const uint32_t k = __builtin_amdgcn_readfirstlane(find_tensor(s_start, count, c));
-        Desc d;
-        d.a = reinterpret_cast<void *>(uniform64(reinterpret_cast<uint64_t>(s_desc[k].a)));
-        d.b = reinterpret_cast<void *>(uniform64(reinterpret_cast<uint64_t>(s_desc[k].b)));
-        d.c = reinterpret_cast<const void *>(uniform64(reinterpret_cast<uint64_t>(s_desc[k].c)));
-        d.n = uniform64(s_desc[k].n);
-        const uint64_t lc = c - __builtin_amdgcn_readfirstlane(s_start[k]);
+        const uint32_t k = count > 1 ? find_tensor(tab.chunk_start, count, c) : 0u;
+        const Desc d = tab.t[k];
+        const uint64_t lc = c - tab.chunk_start[k];
         const uint32_t pre = misalign_elems(d.a);
         const bool vec = coaligned(d.a, d.b, d.c, c_bytes);
         if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {

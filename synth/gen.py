@@ -122,7 +122,16 @@ def _device_lib():
         _device.synth_fill_device.restype = ctypes.c_int
         _device.synth_fill_device.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_uint64, ctypes.c_uint64,
                                               ctypes.POINTER(_Spec), ctypes.c_void_p]
+        _device.synth_copy_device.restype = ctypes.c_int
+        _device.synth_copy_device.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
     return _device
+
+
+def copy_device(dst: int, src: int, nbytes: int, stream: int) -> None:
+    """Enqueue a plain device-to-device copy kernel (reference traffic for counter calibration)."""
+    rc = _device_lib().synth_copy_device(ctypes.c_void_p(dst), ctypes.c_void_p(src), nbytes, ctypes.c_void_p(stream))
+    if rc:
+        raise RuntimeError(f"synth_copy_device failed ({rc})")
 
 
 def fill_host(spec: Spec, dtype: str, n: int, first: int = 0) -> np.ndarray:
