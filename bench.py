@@ -152,6 +152,33 @@ def main() -> int:
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
 
+    # ---- the same mini-batch with fused edges (decay inside micro-batch 0's folds, update inside the last) ----
+    def one_step_fused() -> None:
+        hb.begin_step_fused()
+        for i in range(w.N):
+            for li in w.backward_layers():
+                if i == w.N - 1:
+                    hb.fold_layer_last_apply(li, w.N, w.lr, w.eps, w.beta1, w.beta2)
+                elif i == 0:
+                    hb.fold_layer_first(li, w.N, w.beta1, w.beta2)
+                else:
+                    hb.fold_layer(li, w.N, w.beta1, w.beta2)
+
+    fused = None
+    if w.N > 1:
+        one_step_fused()
+        hb.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step_fused()
+        hb.synchronize()
+        fused_ms = (time.perf_counter() - t1) / args.steps * 1e3
+        fused_bytes = (w.N * (16 + w.grad_bytes) + 8) * w.P       # no decay pass; the update adds theta r+w only
+        fused = {"ms_per_step": round(fused_ms, 3), "bytes_per_step": fused_bytes,
+                 "value": round(fused_bytes / (fused_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                 "params_per_s": round(w.P / (fused_ms * 1e-3), 1),
+                 "note": "same results bit for bit; adama_fold_first_multi / adama_fold_last_apply_multi at the edges"}
+
     # ---- live per-launch timing of the dominant kernel, HIP events on the launch stream ----
     for _ in range(min(2, args.steps)):
         one_step(True)
@@ -188,6 +215,7 @@ def main() -> int:
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},
+        "fused_edges": fused,
         "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
                         "whole_model_bytes": w.P * w.grad_bytes},

@@ -10,6 +10,12 @@
  *     N x layers x adama_fold*    m += (1-beta1) g, v += (1-beta2) g^2, g = grad/N   (Alg. 2, inner body)
  *     adama_apply                 bias-corrected parameter update     (Alg. 2, "Update")
  *
+ * or, with the same results bit for bit and 24 fewer bytes of memory traffic per parameter,
+ *
+ *     layers x adama_fold_first*         micro-batch 0: the decay rides along with the fold
+ *     (N-2) x layers x adama_fold*       micro-batches 1 .. N-2
+ *     layers x adama_fold_last_apply*    micro-batch N-1: the update rides along with the fold
+ *
  * Conventions common to every call
  *  - All data pointers are DEVICE pointers owned by the caller; `list` arrays of
  *    descriptors are HOST memory and are consumed before the call returns.
@@ -59,6 +65,15 @@ typedef struct {
     size_t n;
 } adama_tensor;
 
+/* One tensor of a fused fold+update list. */
+typedef struct {
+    float *theta;      /* device, n floats, read and written */
+    float *m;          /* device, n floats, read and written */
+    float *v;          /* device, n floats, read and written */
+    const void *grad;  /* device, n elements of the list's gradient dtype, read only */
+    size_t n;
+} adama_update_tensor;
+
 /* One tensor of a state list (decay / update). theta may be NULL for adama_begin_step_multi. */
 typedef struct {
     float *theta;      /* device, n floats, read and written by adama_apply_multi */
@@ -93,6 +108,30 @@ adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, s
 adama_status adama_fold_multi(const adama_tensor *list, int count, adama_dtype gdt, int N,
                               double beta1, double beta2, hipStream_t stream);
 
+/* Alg. 1 writes the decay and the accumulation as one statement, m_t = beta1 m_{t-1} + (1-beta1) sum_i g_i:
+ * the fold of the mini-batch's FIRST micro-batch with the decay of Alg. 2's first line applied on the
+ * way,
+ *     m[k] <- beta1*m[k] + (1-beta1) g,  v[k] <- beta2*v[k] + (1-beta2) g^2,   g = grad[k]/N
+ * with the product beta*m rounded before the addition, so the result is bit-identical to
+ * adama_begin_step followed by adama_fold, at the traffic of the fold alone.  Call it instead of
+ * adama_begin_step + adama_fold for every tensor in micro-batch 0.  beta1, beta2 in [0, 1). */
+adama_status adama_fold_first(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N,
+                              double beta1, double beta2, hipStream_t stream);
+adama_status adama_fold_first_multi(const adama_tensor *list, int count, adama_dtype gdt, int N,
+                                    double beta1, double beta2, hipStream_t stream);
+
+/* The fold of the mini-batch's LAST micro-batch followed, element by element, by the Update of Alg. 2
+ * on the freshly folded moments (m and v are rounded to float32 before the update uses them):
+ * bit-identical to adama_fold followed by adama_apply with step counter t >= 1, at 8 fewer bytes of
+ * traffic per parameter.  Call it instead of adama_fold + adama_apply for every tensor in
+ * micro-batch N-1.  Arguments as adama_fold and adama_apply. */
+adama_status adama_fold_last_apply(float *theta, float *m, float *v, const void *grad, adama_dtype gdt,
+                                   size_t n, int N, double lr, double eps, double beta1, double beta2,
+                                   long long t, hipStream_t stream);
+adama_status adama_fold_last_apply_multi(const adama_update_tensor *list, int count, adama_dtype gdt, int N,
+                                         double lr, double eps, double beta1, double beta2, long long t,
+                                         hipStream_t stream);
+
 /* Alg. 2, "Update" (same as Alg. 1), after the last fold of mini-batch t >= 1:
  *     m_hat <- m[k] / (1 - beta1^t);  v_hat <- v[k] / (1 - beta2^t)
  *     theta[k] <- theta[k] - lr * m_hat / (sqrt(v_hat) + eps)
@@ -109,7 +148,7 @@ adama_status adama_apply_multi(const adama_state *list, int count, double lr, do
 const char *adama_last_error(void);
 
 /* Number of tensors one launch's descriptor table holds. */
-#define ADAMA_MAX_TENSORS_PER_LAUNCH 96
+#define ADAMA_MAX_TENSORS_PER_LAUNCH 80
 int adama_max_tensors_per_launch(void);
 
 /* Host-only: the launch policy compiled into the library, for benchmark labels.  A launch whose
@@ -122,12 +161,13 @@ void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems
  * Host-only check of the launch geometry (no device needed, nothing is dereferenced): walks every
  * (launch, chunk, thread, access) the kernels would issue for `list` and adds 1 to touched[k][e]
  * for each element e of tensor k an access covers (touched[k] is a host array of list[k].n bytes,
- * zero-filled by the caller).  op: 0 decay, 1 fold, 2 apply; for op != 1 the three pointers of
- * each adama_tensor stand for the op's three arrays.  *vector_accesses and *scalar_accesses count
- * 16-byte and single-element accesses.  Returns ADAMA_ERR_INVALID_ARG if an access would leave a
- * tensor or a vector access would be misaligned.  Used by the CPU test-suite.
+ * zero-filled by the caller).  op: 0 decay (m, v), 1 fold (m, v, grad), 2 apply (theta, m, v),
+ * 3 fold_first (m, v, grad), 4 fold_last_apply (theta, m, v, grad); fields an op does not use are
+ * ignored.  *vector_accesses and *scalar_accesses count 16-byte and single-element accesses.
+ * Returns ADAMA_ERR_INVALID_ARG if an access would leave a tensor or a vector access would be
+ * misaligned.  Used by the CPU test-suite.
  */
-adama_status adama_debug_walk(const adama_tensor *list, int count, int op, adama_dtype gdt,
+adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op, adama_dtype gdt,
                               unsigned char *const *touched, unsigned long long *vector_accesses,
                               unsigned long long *scalar_accesses, int *launches);
 

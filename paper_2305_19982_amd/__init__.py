@@ -10,6 +10,10 @@ from .binding import (  # noqa: F401
     adama_begin_step,
     adama_begin_step_multi,
     adama_fold,
+    adama_fold_first,
+    adama_fold_first_multi,
+    adama_fold_last_apply,
+    adama_fold_last_apply_multi,
     adama_fold_multi,
     adama_last_error,
     adama_max_tensors_per_launch,

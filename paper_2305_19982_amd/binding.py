@@ -35,6 +35,11 @@ class adama_tensor(ctypes.Structure):
     _fields_ = [("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("n", ctypes.c_size_t)]
 
 
+class adama_update_tensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("grad", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
 class adama_state(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_size_t)]
 
@@ -59,13 +64,19 @@ def load() -> ctypes.CDLL:
     lib.adama_begin_step_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, vp]
     lib.adama_fold.argtypes = [vp, vp, vp, i32, sz, i32, dbl, dbl, vp]
     lib.adama_fold_multi.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, dbl, dbl, vp]
+    lib.adama_fold_first.argtypes = [vp, vp, vp, i32, sz, i32, dbl, dbl, vp]
+    lib.adama_fold_first_multi.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, dbl, dbl, vp]
+    lib.adama_fold_last_apply.argtypes = [vp, vp, vp, vp, i32, sz, i32, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adama_fold_last_apply_multi.argtypes = [ctypes.POINTER(adama_update_tensor), i32, i32, i32, dbl, dbl, dbl,
+                                                dbl, i64, vp]
     lib.adama_apply.argtypes = [vp, vp, vp, sz, dbl, dbl, dbl, dbl, i64, vp]
     lib.adama_apply_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, i64, vp]
-    lib.adama_debug_walk.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, ctypes.POINTER(vp),
+    lib.adama_debug_walk.argtypes = [ctypes.POINTER(adama_update_tensor), i32, i32, i32, ctypes.POINTER(vp),
                                      ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_ulonglong),
                                      ctypes.POINTER(i32)]
     for name in ("adama_begin_step", "adama_begin_step_multi", "adama_fold", "adama_fold_multi", "adama_apply",
-                 "adama_apply_multi", "adama_debug_walk"):
+                 "adama_apply_multi", "adama_fold_first", "adama_fold_first_multi", "adama_fold_last_apply",
+                 "adama_fold_last_apply_multi", "adama_debug_walk"):
         getattr(lib, name).restype = i32
     lib.adama_last_error.restype = ctypes.c_char_p
     lib.adama_last_error.argtypes = []
@@ -113,6 +124,14 @@ def tensor_list(entries) -> ctypes.Array:
     return arr
 
 
+def update_list(entries) -> ctypes.Array:
+    """Host array of adama_update_tensor from (theta, m, v, grad, n) tuples; reusable across calls."""
+    arr = (adama_update_tensor * len(entries))()
+    for i, (th, m, v, g, n) in enumerate(entries):
+        arr[i] = adama_update_tensor(_ptr(th), _ptr(m), _ptr(v), _ptr(g), int(n))
+    return arr
+
+
 def state_list(entries) -> ctypes.Array:
     """Host array of adama_state from (theta, m, v, n) tuples; reusable across calls."""
     arr = (adama_state * len(entries))()
@@ -142,6 +161,31 @@ def adama_fold_multi(lst, count: int | None, gdt, N: int, beta1: float, beta2: f
                                    beta2, stream))
 
 
+def adama_fold_first(m, v, grad, gdt, n: int, N: int, beta1: float, beta2: float, stream: int = 0) -> None:
+    _check(load().adama_fold_first(_ptr(m), _ptr(v), _ptr(grad), DTYPES.get(gdt, gdt), n, N, beta1, beta2, stream))
+
+
+def adama_fold_first_multi(lst, count: int | None, gdt, N: int, beta1: float, beta2: float, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = tensor_list(lst)
+    _check(load().adama_fold_first_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N, beta1,
+                                         beta2, stream))
+
+
+def adama_fold_last_apply(theta, m, v, grad, gdt, n: int, N: int, lr: float, eps: float, beta1: float, beta2: float,
+                          t: int, stream: int = 0) -> None:
+    _check(load().adama_fold_last_apply(_ptr(theta), _ptr(m), _ptr(v), _ptr(grad), DTYPES.get(gdt, gdt), n, N, lr, eps,
+                                        beta1, beta2, t, stream))
+
+
+def adama_fold_last_apply_multi(lst, count: int | None, gdt, N: int, lr: float, eps: float, beta1: float,
+                                beta2: float, t: int, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = update_list(lst)
+    _check(load().adama_fold_last_apply_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N, lr,
+                                              eps, beta1, beta2, t, stream))
+
+
 def adama_apply(theta, m, v, n: int, lr: float, eps: float, beta1: float, beta2: float, t: int,
                 stream: int = 0) -> None:
     _check(load().adama_apply(_ptr(theta), _ptr(m), _ptr(v), n, lr, eps, beta1, beta2, t, stream))
@@ -155,12 +199,13 @@ def adama_apply_multi(lst, count: int | None, lr: float, eps: float, beta1: floa
 
 
 def adama_debug_walk(entries, op: int, gdt):
-    """Host-only geometry walk.  entries: (a, b, c, n) integer addresses (never dereferenced).
-    Returns (touch counts per tensor as bytearrays, vector accesses, scalar accesses, launches)."""
-    lst = tensor_list(entries)
-    bufs = [(ctypes.c_ubyte * max(1, int(e[3])))() for e in entries]
+    """Host-only geometry walk.  entries: (theta, m, v, grad, n) integer addresses (never dereferenced;
+    fields the op does not use may be None).  Returns (touch counts per tensor as bytes, vector accesses,
+    scalar accesses, launches)."""
+    lst = update_list(entries)
+    bufs = [(ctypes.c_ubyte * max(1, int(e[4])))() for e in entries]
     ptrs = (ctypes.c_void_p * max(1, len(entries)))(*[ctypes.addressof(b) for b in bufs])
     nvec, nsc, nl = ctypes.c_ulonglong(0), ctypes.c_ulonglong(0), ctypes.c_int(0)
     _check(load().adama_debug_walk(lst, len(entries), op, DTYPES.get(gdt, gdt), ptrs, ctypes.byref(nvec),
                                    ctypes.byref(nsc), ctypes.byref(nl)))
-    return [bytes(b)[:int(e[3])] for b, e in zip(bufs, entries)], nvec.value, nsc.value, nl.value
+    return [bytes(b)[:int(e[4])] for b, e in zip(bufs, entries)], nvec.value, nsc.value, nl.value

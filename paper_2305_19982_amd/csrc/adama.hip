@@ -16,6 +16,7 @@ using namespace adama;
 
 static_assert(ADAMA_MAX_TENSORS_PER_LAUNCH == kMaxTensors, "header and kernel table size disagree");
 static_assert(sizeof(Table<kMaxTensors>) + sizeof(Scalars) <= 4096, "launch table must fit the kernel argument block");
+static_assert(sizeof(Desc) == 40, "descriptor layout");
 static_assert((int)ADAMA_F32 == kF32 && (int)ADAMA_BF16 == kBF16 && (int)ADAMA_F16 == kF16, "dtype codes");
 
 namespace {
@@ -43,7 +44,7 @@ constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long 
 constexpr uint32_t kMaxGrid = 1u << 30;
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 
-uint32_t grad_bytes(int op, int gdt) { return op == kDecay ? 0u : (op == kApply || gdt == kF32) ? 4u : 2u; }
+uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF32 ? 4u : 2u; }
 
 // One launch: tensors [first, first+count) of the caller's list with their chunk prefix.
 struct Batch {
@@ -72,7 +73,7 @@ adama_status for_each_batch(const Desc *descs, int count, Emit &&emit)
         uint64_t start = 0;
         for (int j = 0; j < k; ++j) {
             b.tab.chunk_start[j] = (uint32_t)start;
-            start += chunks_of(misalign_elems(b.tab.t[j].a), b.tab.t[j].n, chunk);
+            start += chunks_of(misalign_elems(b.tab.t[j].s[0]), b.tab.t[j].n, chunk);
         }
         b.tab.chunk_start[k] = (uint32_t)start;
         for (int j = k + 1; j < kMaxTensors + 17; ++j) b.tab.chunk_start[j] = 0xFFFFFFFFu;
@@ -102,15 +103,26 @@ void launch_u(const Batch &b, const Scalars &sc, unsigned grid, hipStream_t stre
     else launch_one<OpK, GT, kUSmall>(b, sc, grid, stream);
 }
 
+template <int OpK>
+void launch_gdt(int gdt, const Batch &b, const Scalars &sc, unsigned grid, hipStream_t stream)
+{
+    if constexpr (!op_has_grad(OpK)) launch_u<OpK, kF32>(b, sc, grid, stream);
+    else if (gdt == kF32) launch_u<OpK, kF32>(b, sc, grid, stream);
+    else if (gdt == kBF16) launch_u<OpK, kBF16>(b, sc, grid, stream);
+    else launch_u<OpK, kF16>(b, sc, grid, stream);
+}
+
 adama_status launch_all(int op, int gdt, const Desc *descs, int count, const Scalars &sc, hipStream_t stream)
 {
     return for_each_batch(descs, count, [&](const Batch &b, int) -> adama_status {
         const unsigned grid = b.total < kMaxGrid ? b.total : kMaxGrid;
-        if (op == kDecay) launch_u<kDecay, kF32>(b, sc, grid, stream);
-        else if (op == kApply) launch_u<kApply, kF32>(b, sc, grid, stream);
-        else if (gdt == kF32) launch_u<kFold, kF32>(b, sc, grid, stream);
-        else if (gdt == kBF16) launch_u<kFold, kBF16>(b, sc, grid, stream);
-        else launch_u<kFold, kF16>(b, sc, grid, stream);
+        switch (op) {
+        case kDecay: launch_gdt<kDecay>(gdt, b, sc, grid, stream); break;
+        case kFold: launch_gdt<kFold>(gdt, b, sc, grid, stream); break;
+        case kApply: launch_gdt<kApply>(gdt, b, sc, grid, stream); break;
+        case kFoldFirst: launch_gdt<kFoldFirst>(gdt, b, sc, grid, stream); break;
+        default: launch_gdt<kFoldLastApply>(gdt, b, sc, grid, stream); break;
+        }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(ADAMA_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
         return ADAMA_OK;
@@ -146,7 +158,7 @@ adama_status check_dtype(adama_dtype gdt)
 
 #define ADAMA_TRY(expr) do { adama_status st_ = (expr); if (st_ != ADAMA_OK) return st_; } while (0)
 
-adama_status check_fold_args(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1, double beta2)
+adama_status check_fold_hyper(adama_dtype gdt, int count, const void *list, int N, double beta1, double beta2)
 {
     ADAMA_TRY(check_dtype(gdt));
     if (count < 0) return fail(ADAMA_ERR_INVALID_ARG, "count = %d is negative", count);
@@ -154,9 +166,30 @@ adama_status check_fold_args(const adama_tensor *list, int count, adama_dtype gd
     if (N < 1) return fail(ADAMA_ERR_INVALID_ARG, "N = %d: the number of micro-batches must be >= 1", N);
     if (!unit_interval(beta1) || !unit_interval(beta2))
         return fail(ADAMA_ERR_INVALID_ARG, "beta1 = %g, beta2 = %g must lie in [0, 1)", beta1, beta2);
+    return ADAMA_OK;
+}
+
+adama_status check_fold_args(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1, double beta2)
+{
+    ADAMA_TRY(check_fold_hyper(gdt, count, list, N, beta1, beta2));
     const size_t gb = gdt == ADAMA_F32 ? 4 : 2;
     for (int i = 0; i < count; ++i) {
         ADAMA_TRY(check_len(i, list[i].n));
+        ADAMA_TRY(check_array("m", i, list[i].m, 4, list[i].n));
+        ADAMA_TRY(check_array("v", i, list[i].v, 4, list[i].n));
+        ADAMA_TRY(check_array("grad", i, list[i].grad, gb, list[i].n));
+    }
+    return ADAMA_OK;
+}
+
+adama_status check_update_args(const adama_update_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                               double beta2)
+{
+    ADAMA_TRY(check_fold_hyper(gdt, count, list, N, beta1, beta2));
+    const size_t gb = gdt == ADAMA_F32 ? 4 : 2;
+    for (int i = 0; i < count; ++i) {
+        ADAMA_TRY(check_len(i, list[i].n));
+        ADAMA_TRY(check_array("theta", i, list[i].theta, 4, list[i].n));
         ADAMA_TRY(check_array("m", i, list[i].m, 4, list[i].n));
         ADAMA_TRY(check_array("v", i, list[i].v, 4, list[i].n));
         ADAMA_TRY(check_array("grad", i, list[i].grad, gb, list[i].n));
@@ -190,17 +223,49 @@ adama_status check_apply_hyper(double lr, double eps, double beta1, double beta2
 // Descriptor lists are converted in pieces of this many tensors so that no call allocates.
 constexpr int kPiece = 4 * kMaxTensors;
 
-Scalars fold_scalars(int N, double beta1, double beta2)
+void set_fold_scalars(Scalars &sc, int N, double beta1, double beta2)
 {
     const double dn = (double)N;
-    return Scalars{(float)((1.0 - beta1) / dn), (float)((1.0 - beta2) / (dn * dn)), 0.0f};
+    sc.c1 = (float)((1.0 - beta1) / dn);
+    sc.c2 = (float)((1.0 - beta2) / (dn * dn));
 }
 
-Scalars apply_scalars(double lr, double eps, double beta1, double beta2, long long t)
+void set_decay_scalars(Scalars &sc, double beta1, double beta2)
+{
+    sc.d1 = (float)beta1;
+    sc.d2 = (float)beta2;
+}
+
+void set_apply_scalars(Scalars &sc, double lr, double eps, double beta1, double beta2, long long t)
 {
     const double bias1 = 1.0 - std::pow(beta1, (double)t);
     const double bias2 = 1.0 - std::pow(beta2, (double)t);
-    return Scalars{(float)(lr / bias1), (float)(1.0 / std::sqrt(bias2)), (float)eps};
+    sc.step = (float)(lr / bias1);
+    sc.rs2 = (float)(1.0 / std::sqrt(bias2));
+    sc.eps = (float)eps;
+}
+
+// Converts the caller's list piece by piece with `to_desc` and launches `op` over it.
+template <typename T, typename ToDesc>
+adama_status run_list(int op, int gdt, const T *list, int count, const Scalars &sc, hipStream_t stream, ToDesc &&to_desc)
+{
+    Desc piece[kPiece];
+    for (int i = 0; i < count; i += kPiece) {
+        const int k = count - i < kPiece ? count - i : kPiece;
+        for (int j = 0; j < k; ++j) piece[j] = to_desc(list[i + j]);
+        ADAMA_TRY(launch_all(op, gdt, piece, k, sc, stream));
+    }
+    return ADAMA_OK;
+}
+
+Desc fold_desc(const adama_tensor &t) { return Desc{{t.m, t.v, nullptr}, t.grad, t.n}; }
+Desc update_desc(const adama_update_tensor &t) { return Desc{{t.theta, t.m, t.v}, t.grad, t.n}; }
+
+// The arrays op `op` uses, out of the superset descriptor of the geometry walk.
+Desc walk_desc(int op, const adama_update_tensor &t)
+{
+    if (op_states(op) == 3) return Desc{{t.theta, t.m, t.v}, op_has_grad(op) ? t.grad : nullptr, t.n};
+    return Desc{{t.m, t.v, nullptr}, op_has_grad(op) ? t.grad : nullptr, t.n};
 }
 
 }  // namespace
@@ -223,14 +288,9 @@ adama_status adama_fold_multi(const adama_tensor *list, int count, adama_dtype g
                               double beta2, hipStream_t stream)
 {
     ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
-    const Scalars sc = fold_scalars(N, beta1, beta2);
-    Desc piece[kPiece];
-    for (int i = 0; i < count; i += kPiece) {
-        int k = count - i < kPiece ? count - i : kPiece;
-        for (int j = 0; j < k; ++j) piece[j] = Desc{list[i + j].m, list[i + j].v, list[i + j].grad, list[i + j].n};
-        ADAMA_TRY(launch_all(kFold, (int)gdt, piece, k, sc, stream));
-    }
-    return ADAMA_OK;
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2);
+    return run_list(kFold, (int)gdt, list, count, sc, stream, fold_desc);
 }
 
 adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N, double beta1,
@@ -240,20 +300,53 @@ adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, s
     return adama_fold_multi(&one, 1, gdt, N, beta1, beta2, stream);
 }
 
+adama_status adama_fold_first_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                                    double beta2, hipStream_t stream)
+{
+    ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2);
+    set_decay_scalars(sc, beta1, beta2);
+    return run_list(kFoldFirst, (int)gdt, list, count, sc, stream, fold_desc);
+}
+
+adama_status adama_fold_first(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N,
+                              double beta1, double beta2, hipStream_t stream)
+{
+    adama_tensor one{m, v, grad, n};
+    return adama_fold_first_multi(&one, 1, gdt, N, beta1, beta2, stream);
+}
+
+adama_status adama_fold_last_apply_multi(const adama_update_tensor *list, int count, adama_dtype gdt, int N,
+                                         double lr, double eps, double beta1, double beta2, long long t,
+                                         hipStream_t stream)
+{
+    ADAMA_TRY(check_update_args(list, count, gdt, N, beta1, beta2));
+    ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2);
+    set_apply_scalars(sc, lr, eps, beta1, beta2, t);
+    return run_list(kFoldLastApply, (int)gdt, list, count, sc, stream, update_desc);
+}
+
+adama_status adama_fold_last_apply(float *theta, float *m, float *v, const void *grad, adama_dtype gdt,
+                                   size_t n, int N, double lr, double eps, double beta1, double beta2,
+                                   long long t, hipStream_t stream)
+{
+    adama_update_tensor one{theta, m, v, grad, n};
+    return adama_fold_last_apply_multi(&one, 1, gdt, N, lr, eps, beta1, beta2, t, stream);
+}
+
 adama_status adama_begin_step_multi(const adama_state *list, int count, double beta1, double beta2,
                                     hipStream_t stream)
 {
     ADAMA_TRY(check_state_args(list, count, false));
     if (!finite_nonneg(beta1) || !finite_nonneg(beta2))
         return fail(ADAMA_ERR_INVALID_ARG, "beta1 = %g, beta2 = %g must be finite and >= 0", beta1, beta2);
-    const Scalars sc{(float)beta1, (float)beta2, 0.0f};
-    Desc piece[kPiece];
-    for (int i = 0; i < count; i += kPiece) {
-        int k = count - i < kPiece ? count - i : kPiece;
-        for (int j = 0; j < k; ++j) piece[j] = Desc{list[i + j].m, list[i + j].v, nullptr, list[i + j].n};
-        ADAMA_TRY(launch_all(kDecay, kF32, piece, k, sc, stream));
-    }
-    return ADAMA_OK;
+    Scalars sc{};
+    set_decay_scalars(sc, beta1, beta2);
+    return run_list(kDecay, kF32, list, count, sc, stream,
+                    [](const adama_state &t) { return Desc{{t.m, t.v, nullptr}, nullptr, t.n}; });
 }
 
 adama_status adama_begin_step(float *m, float *v, size_t n, double beta1, double beta2, hipStream_t stream)
@@ -267,14 +360,10 @@ adama_status adama_apply_multi(const adama_state *list, int count, double lr, do
 {
     ADAMA_TRY(check_state_args(list, count, true));
     ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
-    const Scalars sc = apply_scalars(lr, eps, beta1, beta2, t);
-    Desc piece[kPiece];
-    for (int i = 0; i < count; i += kPiece) {
-        int k = count - i < kPiece ? count - i : kPiece;
-        for (int j = 0; j < k; ++j) piece[j] = Desc{list[i + j].theta, list[i + j].m, list[i + j].v, list[i + j].n};
-        ADAMA_TRY(launch_all(kApply, kF32, piece, k, sc, stream));
-    }
-    return ADAMA_OK;
+    Scalars sc{};
+    set_apply_scalars(sc, lr, eps, beta1, beta2, t);
+    return run_list(kApply, kF32, list, count, sc, stream,
+                    [](const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; });
 }
 
 adama_status adama_apply(float *theta, const float *m, const float *v, size_t n, double lr, double eps,
@@ -284,43 +373,44 @@ adama_status adama_apply(float *theta, const float *m, const float *v, size_t n,
     return adama_apply_multi(&one, 1, lr, eps, beta1, beta2, t, stream);
 }
 
-adama_status adama_debug_walk(const adama_tensor *list, int count, int op, adama_dtype gdt,
+adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op, adama_dtype gdt,
                               unsigned char *const *touched, unsigned long long *vector_accesses,
                               unsigned long long *scalar_accesses, int *launches)
 {
-    if (op < kDecay || op > kApply) return fail(ADAMA_ERR_INVALID_ARG, "op = %d", op);
+    if (op < 0 || op >= kNumOps) return fail(ADAMA_ERR_INVALID_ARG, "op = %d", op);
     ADAMA_TRY(check_dtype(gdt));
     if (count < 0 || (count > 0 && (!list || !touched))) return fail(ADAMA_ERR_INVALID_ARG, "bad list");
-    const uint32_t cb = grad_bytes(op, (int)gdt);
+    const uint32_t gb = grad_bytes(op, (int)gdt);
+    const int ns = op_states(op);
     unsigned long long nvec = 0, nsc = 0;
     int nlaunch = 0;
     for (int i0 = 0; i0 < count; i0 += kPiece) {
-        int kp = count - i0 < kPiece ? count - i0 : kPiece;
+        const int kp = count - i0 < kPiece ? count - i0 : kPiece;
         Desc piece[kPiece];
-        for (int j = 0; j < kp; ++j) piece[j] = Desc{list[i0 + j].m, list[i0 + j].v, list[i0 + j].grad, list[i0 + j].n};
+        for (int j = 0; j < kp; ++j) piece[j] = walk_desc(op, list[i0 + j]);
         adama_status st = for_each_batch(piece, kp, [&](const Batch &b, int first) -> adama_status {
             ++nlaunch;
             const uint32_t chunk = kBlock * kGroup * b.u;
             const uint32_t cnt = b.tab.count;
             const int base = i0 + first;   // list index of the batch's first tensor
             for (uint32_t c = 0; c < b.total; ++c) {
-                const uint32_t k = find_tensor(b.tab.chunk_start, cnt, c);
+                const uint32_t k = cnt > 1 ? find_tensor(b.tab.chunk_start, cnt, c) : 0u;
                 const Desc &d = b.tab.t[k];
                 const uint64_t lc = c - b.tab.chunk_start[k];
-                const uint32_t pre = misalign_elems(d.a);
-                const bool vec = coaligned(d.a, d.b, d.c, cb);
+                const uint32_t pre = misalign_elems(d.s[0]);
+                const bool vec = coaligned(d, ns, gb);
                 unsigned char *tch = touched[base + (int)k];
                 const bool interior = chunk_is_interior(vec, pre, d.n, lc, chunk);
                 for (int u = 0; u < b.u; ++u) {
                     for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
                         const uint64_t coord = lc * chunk + (uint64_t)(u * kBlock + tid) * kGroup;
-                        int kind = interior ? 2 : group_kind(vec, pre, d.n, coord);
+                        const int kind = interior ? 2 : group_kind(vec, pre, d.n, coord);
                         if (kind == 2) {
                             if (coord < pre) return fail(ADAMA_ERR_INVALID_ARG, "vector access before tensor %d", base + (int)k);
                             const uint64_t e = coord - pre;
                             if (e + kGroup > d.n) return fail(ADAMA_ERR_INVALID_ARG, "vector access past tensor %d", base + (int)k);
-                            const bool ok = aligned_to((const float *)d.a + e, 16) && aligned_to((const float *)d.b + e, 16) &&
-                                            (cb == 0 || aligned_to((const char *)d.c + e * cb, 4 * cb));
+                            bool ok = gb == 0 || aligned_to((const char *)d.g + e * gb, 4 * gb);
+                            for (int a = 0; a < ns; ++a) ok = ok && aligned_to((const float *)d.s[a] + e, 16);
                             if (!ok) return fail(ADAMA_ERR_INVALID_ARG, "misaligned vector access in tensor %d", base + (int)k);
                             for (int j = 0; j < kGroup; ++j) ++tch[e + j];
                             ++nvec;

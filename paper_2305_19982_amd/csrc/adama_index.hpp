@@ -5,7 +5,7 @@
 // tensor sits at coordinate pre + e, where pre (0..3) is the number of float32
 // elements by which the tensor's first state array is past a 16-byte boundary.
 // Coordinates that are multiples of 4 therefore fall on 16-byte boundaries of
-// the state arrays, whatever the tensor's start address.  When the other two
+// the state arrays, whatever the tensor's start address.  When the other
 // arrays of the tensor share that misalignment ("co-aligned"), every 4-element
 // group wholly inside the tensor can be moved with 16-byte accesses; the at
 // most one partial group at either end, and tensors that are not co-aligned,
@@ -24,15 +24,24 @@ namespace adama {
 
 constexpr int kBlock = 256;       // threads per workgroup: four 64-wide wavefronts
 constexpr int kGroup = 4;         // elements per 16-byte float32 access
-constexpr int kMaxTensors = 96;   // descriptors per launch (table lives in the kernel argument block)
+constexpr int kMaxTensors = 80;   // descriptors per launch (table lives in the kernel argument block)
 
-enum Op : int { kDecay = 0, kFold = 1, kApply = 2 };
+// The steps of the path.  "First" folds perform the mini-batch's decay on the way (micro-batch 0),
+// "LastApply" folds perform the parameter update on the way (micro-batch N-1).
+enum Op : int { kDecay = 0, kFold = 1, kApply = 2, kFoldFirst = 3, kFoldLastApply = 4, kNumOps = 5 };
 
-// The three arrays of one tensor.  decay: a=m, b=v.  fold: a=m, b=v, c=grad.  apply: a=theta, b=m, c=v.
+// Number of float32 state arrays an op touches, and whether it reads a gradient.
+//   decay, fold, fold_first : s = {m, v}
+//   apply, fold_last_apply  : s = {theta, m, v}
+ADAMA_HD constexpr int op_states(int op) { return (op == kApply || op == kFoldLastApply) ? 3 : 2; }
+ADAMA_HD constexpr bool op_has_grad(int op) { return op == kFold || op == kFoldFirst || op == kFoldLastApply; }
+// Bit k set: state array k is written back.
+ADAMA_HD constexpr int op_store_mask(int op) { return op == kApply ? 1 : op == kFoldLastApply ? 7 : 3; }
+
+// The arrays of one tensor: up to three float32 state arrays and the gradient.
 struct Desc {
-    void *a;
-    void *b;
-    const void *c;
+    void *s[3];
+    const void *g;
     uint64_t n;
 };
 
@@ -50,15 +59,16 @@ struct Table {
 // Misalignment of the first state array, in float32 elements (0..3).
 ADAMA_HD uint32_t misalign_elems(const void *a) { return (uint32_t)(((uintptr_t)a >> 2) & (kGroup - 1)); }
 
-// True when b (float32) and c (elements of c_bytes bytes, or unused when c_bytes == 0) reach a
-// 16-byte boundary at the same element index as a does.
-ADAMA_HD bool coaligned(const void *a, const void *b, const void *c, uint32_t c_bytes)
+// True when every state array of the op, and the gradient (elements of g_bytes bytes) if the op
+// reads one, reaches a 16-byte boundary at the same element index as the first state array does.
+ADAMA_HD bool coaligned(const Desc &d, int n_states, uint32_t g_bytes)
 {
-    uint32_t pre = misalign_elems(a);
-    if ((((uintptr_t)b >> 2) & (kGroup - 1)) != pre) return false;
-    if (c_bytes == 0) return true;
-    uint32_t shift = c_bytes == 4 ? 2 : 1;
-    return (((uintptr_t)c >> shift) & (kGroup - 1)) == pre;
+    const uint32_t pre = misalign_elems(d.s[0]);
+    for (int k = 1; k < n_states; ++k)
+        if ((((uintptr_t)d.s[k] >> 2) & (kGroup - 1)) != pre) return false;
+    if (g_bytes == 0) return true;
+    const uint32_t shift = g_bytes == 4 ? 2 : 1;
+    return (((uintptr_t)d.g >> shift) & (kGroup - 1)) == pre;
 }
 
 ADAMA_HD uint64_t chunks_of(uint32_t pre, uint64_t n, uint32_t chunk)

@@ -1,21 +1,25 @@
 // Device kernels of libadama (gfx950).
 //
-// One kernel template serves the three memory-bound elementwise steps of AdamA
+// One kernel template serves the memory-bound elementwise steps of AdamA
 // (paper Alg. 2): the once-per-mini-batch moment decay, the per-layer
-// per-micro-batch fold, and the bias-corrected update.  Each is a pure stream:
+// per-micro-batch fold, the bias-corrected update, and the two fused edge
+// forms (decay inside the first micro-batch's fold, update inside the last
+// one's).  Each is a pure stream:
 //
-//   decay : read m, v            write m, v        16 B / element
-//   fold  : read grad, m, v      write m, v        16 + sizeof(grad) B / element
-//   apply : read theta, m, v     write theta       16 B / element
+//   decay           : read m, v                 write m, v          16 B / element
+//   fold            : read grad, m, v           write m, v          16 + sizeof(grad)
+//   apply           : read theta, m, v          write theta         16
+//   fold_first      : as fold (the decay rides along)               16 + sizeof(grad)
+//   fold_last_apply : read grad, theta, m, v    write theta, m, v   24 + sizeof(grad)
 //
 // so the design goal is HBM bandwidth, not arithmetic: no MFMA, no LDS tiling of
 // data (there is no reuse), only wide coalesced accesses and enough of them in
-// flight.  A workgroup of 256 threads walks chunks of 1024*U elements; inside
-// an interior chunk each thread issues all of its U 16-byte loads per array
-// before the first use, so a wavefront has 2U..3U independent 1-KiB requests
-// outstanding.  The table of tensors of the launch arrives in the kernel
-// argument block, together with the per-tensor chunk prefix that maps a chunk
-// number to its tensor; both are read through the scalar cache.
+// flight.  A workgroup of 256 threads handles one chunk of 1024*U elements;
+// inside an interior chunk each thread issues all of its U 16-byte loads per
+// array before the first use, so a wavefront has 2U..4U independent 1-KiB
+// requests outstanding.  The table of tensors of the launch arrives in the
+// kernel argument block, together with the per-tensor chunk prefix that maps a
+// chunk number to its tensor; both are read through the scalar cache.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -31,25 +35,25 @@ typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
 
 enum GradType : int { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
-// Every data pointer of a launch is device global memory.  The descriptors travel through LDS as
-// integers, so the address space is restored here: global (not flat) loads and stores return in
-// order, which lets the hardware counters wait for the oldest of many outstanding loads.
+// Every data pointer of a launch is device global memory; say so, so that the compiler emits global
+// (not flat) loads and stores, which return in order and let the hardware counters wait for the
+// oldest of many outstanding loads.
 #define ADAMA_GLOBAL __attribute__((address_space(1)))
 template <typename T>
-__device__ __forceinline__ ADAMA_GLOBAL T *global_ptr(const void *p, uint64_t elem_offset_bytes = 0)
+__device__ __forceinline__ ADAMA_GLOBAL T *global_ptr(const void *p, uint64_t byte_offset = 0)
 {
-    return (ADAMA_GLOBAL T *)(reinterpret_cast<uintptr_t>(p) + elem_offset_bytes);
+    return (ADAMA_GLOBAL T *)(reinterpret_cast<uintptr_t>(p) + byte_offset);
 }
 
-// Policy bits of a kernel instantiation: which streams use non-temporal accesses, and whether interior
-// chunks address memory through buffer descriptors (scalar base + 32-bit lane offset) instead of
-// 64-bit per-lane global addresses.
-enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4, kBufferAddressing = 8 };
+// Cache-policy bits of a kernel instantiation: which streams use non-temporal accesses.
+enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4 };
 
-// decay: s0 = beta1, s1 = beta2.  fold: s0 = (1-beta1)/N, s1 = (1-beta2)/N^2.
-// apply: s0 = lr/(1-beta1^t), s1 = 1/sqrt(1-beta2^t), s2 = eps.
+// Per-launch scalars, already rounded to float32 from double on the host.
+//   c1 = (1-beta1)/N, c2 = (1-beta2)/N^2            fold, fold_first, fold_last_apply
+//   d1 = beta1, d2 = beta2                           decay, fold_first
+//   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply
 struct Scalars {
-    float s0, s1, s2;
+    float c1, c2, d1, d2, step, rs2, eps;
 };
 
 template <bool NT, typename T>
@@ -64,31 +68,6 @@ __device__ __forceinline__ void st(ADAMA_GLOBAL T *p, T x)
 {
     if constexpr (NT) __builtin_nontemporal_store(x, p);
     else *p = x;
-}
-
-// Buffer-descriptor access to one chunk: base is wave-uniform, `bytes` bounds the range (the hardware
-// drops anything outside it), offsets are 32-bit.  aux bit 1 is the non-temporal hint on gfx950.
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-__device__ __forceinline__ __amdgpu_buffer_rsrc_t chunk_rsrc(const void *base, uint64_t byte_offset, uint32_t bytes)
-{
-    return __builtin_amdgcn_make_buffer_rsrc(reinterpret_cast<void *>(reinterpret_cast<uintptr_t>(base) + byte_offset),
-                                             0, bytes, 0x00020000);
-}
-
-template <bool NT, typename T>
-__device__ __forceinline__ T buf_ld(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset)
-{
-    constexpr int aux = NT ? 2 : 0;
-    if constexpr (sizeof(T) == 16) return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b128(r, byte_offset, 0, aux));
-    else return __builtin_bit_cast(T, __builtin_amdgcn_raw_buffer_load_b64(r, byte_offset, 0, aux));
-}
-
-template <bool NT>
-__device__ __forceinline__ void buf_st(__amdgpu_buffer_rsrc_t r, uint32_t byte_offset, f32x4 x)
-{
-    constexpr int aux = NT ? 2 : 0;
-    __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, x), r, byte_offset, 0, aux);
 }
 
 // ---- gradient storage formats: 4-element vector type, element type, exact widening to float32 ----
@@ -123,63 +102,32 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
     static __device__ __forceinline__ float widen1(_Float16 h) { return (float)h; }
 };
 
-// ---- the arithmetic of the three steps, one element at a time ----
-// Alg. 2 inner body with c1 = (1-beta1)/N, c2 = (1-beta2)/N^2 applied to the raw gradient:
-// m += c1*g, v += c2*g^2.  g*g is exact in float32 for bf16 and fp16 inputs.
-__device__ __forceinline__ void fold1(float &m, float &v, float g, const Scalars &sc)
+// ---- the arithmetic, one element at a time ----
+// s[] holds the element of each state array of the op (see op_states): {m, v} or {theta, m, v}.
+// Every product and sum below is rounded on its own (contraction is off), so a fused edge form
+// produces the very bits the separate steps would.
+//
+//   decay  (Alg. 2, first line of the loop):  m <- beta1*m, v <- beta2*v
+//   fold   (Alg. 2, inner body):              m <- m + c1*g, v <- v + c2*g^2   (g the raw gradient;
+//                                             g*g is exact in float32 for bf16 and fp16 inputs)
+//   apply  (Alg. 2, Update):                  theta <- theta - step*m / (sqrt(v)*rs2 + eps)
+//                                             = theta - lr*m_hat/(sqrt(v_hat)+eps); IEEE sqrt and divide
+template <int OpK>
+__device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars &sc)
 {
-    m = __builtin_fmaf(sc.s0, g, m);
-    v = __builtin_fmaf(sc.s1, g * g, v);
-}
-
-__device__ __forceinline__ void decay1(float &m, float &v, const Scalars &sc)
-{
-    m = sc.s0 * m;
-    v = sc.s1 * v;
-}
-
-// Alg. 2 Update: theta - lr*m_hat/(sqrt(v_hat)+eps) with m_hat = m/(1-beta1^t), v_hat = v/(1-beta2^t),
-// written as theta - s0*m / (sqrt(v)*s1 + eps).  IEEE square root and division.
-__device__ __forceinline__ float apply1(float theta, float m, float v, const Scalars &sc)
-{
-    float denom = __builtin_fmaf(__builtin_sqrtf(v), sc.s1, sc.s2);
-    return theta - (sc.s0 * m) / denom;
-}
-
-// The same three steps on a 16-byte group, element by element.
-__device__ __forceinline__ void fold4(f32x4 &m, f32x4 &v, f32x4 g, const Scalars &sc)
-{
-#pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-        float mj = m[j], vj = v[j];
-        fold1(mj, vj, g[j], sc);
-        m[j] = mj;
-        v[j] = vj;
+    constexpr int im = op_states(OpK) == 3 ? 1 : 0, iv = im + 1;
+    if constexpr (OpK == kDecay || OpK == kFoldFirst) {
+        s[im] = sc.d1 * s[im];
+        s[iv] = sc.d2 * s[iv];
     }
-}
-
-__device__ __forceinline__ void decay4(f32x4 &m, f32x4 &v, const Scalars &sc)
-{
-#pragma unroll
-    for (int j = 0; j < kGroup; ++j) {
-        float mj = m[j], vj = v[j];
-        decay1(mj, vj, sc);
-        m[j] = mj;
-        v[j] = vj;
+    if constexpr (op_has_grad(OpK)) {
+        s[im] = __builtin_fmaf(sc.c1, g, s[im]);
+        s[iv] = __builtin_fmaf(sc.c2, g * g, s[iv]);
     }
-}
-
-__device__ __forceinline__ void apply4(f32x4 &th, f32x4 m, f32x4 v, const Scalars &sc)
-{
-#pragma unroll
-    for (int j = 0; j < kGroup; ++j) th[j] = apply1(th[j], m[j], v[j], sc);
-}
-
-__device__ __forceinline__ uint64_t uniform64(uint64_t x)
-{
-    uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)x);
-    uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(x >> 32));
-    return ((uint64_t)hi << 32) | lo;
+    if constexpr (OpK == kApply || OpK == kFoldLastApply) {
+        const float denom = __builtin_fmaf(__builtin_sqrtf(s[iv]), sc.rs2, sc.eps);
+        s[0] = s[0] - (sc.step * s[im]) / denom;
+    }
 }
 
 // ---- one interior chunk: every group is a full aligned group; all loads first ----
@@ -187,117 +135,36 @@ template <int OpK, int GT, int U, int NT>
 __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint32_t tid, const Scalars &sc)
 {
     constexpr bool ntg = (NT & kNtGradLoad) != 0, ntl = (NT & kNtStateLoad) != 0, nts = (NT & kNtStore) != 0;
-    if constexpr ((NT & kBufferAddressing) != 0) {
-        constexpr uint32_t chunk = kBlock * kGroup * U;
-        __amdgpu_buffer_rsrc_t ra = chunk_rsrc(d.a, e0 * 4, chunk * 4);
-        __amdgpu_buffer_rsrc_t rb = chunk_rsrc(d.b, e0 * 4, chunk * 4);
-        if constexpr (OpK == kFold) {
-            using G = Grad<GT>;
-            constexpr uint32_t gsz = sizeof(typename G::Vec);
-            __amdgpu_buffer_rsrc_t rc = chunk_rsrc(d.c, e0 * sizeof(typename G::Elem), chunk * sizeof(typename G::Elem));
-            typename G::Vec g[U];
-            f32x4 m[U], v[U];
+    constexpr int NS = op_states(OpK);
+    using G = Grad<GT>;
+    ADAMA_GLOBAL f32x4 *S[NS];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                g[u] = buf_ld<ntg, typename G::Vec>(rc, i * gsz);
-                m[u] = buf_ld<ntl, f32x4>(ra, i * 16);
-                v[u] = buf_ld<ntl, f32x4>(rb, i * 16);
-            }
+    for (int k = 0; k < NS; ++k) S[k] = global_ptr<f32x4>(d.s[k], e0 * 4);
+    const ADAMA_GLOBAL typename G::Vec *Gp = global_ptr<typename G::Vec>(d.g, e0 * sizeof(typename G::Elem));
+    typename G::Vec g[U];
+    f32x4 x[NS][U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                fold4(m[u], v[u], G::widen(g[u]), sc);
-                buf_st<nts>(ra, i * 16, m[u]);
-                buf_st<nts>(rb, i * 16, v[u]);
-            }
-        } else if constexpr (OpK == kDecay) {
-            f32x4 m[U], v[U];
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = u * kBlock + tid;
+        if constexpr (op_has_grad(OpK)) g[u] = ld<ntg>(Gp + i);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                m[u] = buf_ld<ntl, f32x4>(ra, i * 16);
-                v[u] = buf_ld<ntl, f32x4>(rb, i * 16);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                decay4(m[u], v[u], sc);
-                buf_st<nts>(ra, i * 16, m[u]);
-                buf_st<nts>(rb, i * 16, v[u]);
-            }
-        } else {
-            __amdgpu_buffer_rsrc_t rc = chunk_rsrc(d.c, e0 * 4, chunk * 4);
-            f32x4 th[U], m[U], v[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                th[u] = buf_ld<ntl, f32x4>(ra, i * 16);
-                m[u] = buf_ld<ntl, f32x4>(rb, i * 16);
-                v[u] = buf_ld<ntl, f32x4>(rc, i * 16);
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                uint32_t i = u * kBlock + tid;
-                apply4(th[u], m[u], v[u], sc);
-                buf_st<nts>(ra, i * 16, th[u]);
-            }
-        }
-        return;
+        for (int k = 0; k < NS; ++k) x[k][u] = ld<ntl>(S[k] + i);
     }
-    ADAMA_GLOBAL f32x4 *A = global_ptr<f32x4>(d.a, e0 * 4);
-    ADAMA_GLOBAL f32x4 *B = global_ptr<f32x4>(d.b, e0 * 4);
-    if constexpr (OpK == kFold) {
-        using G = Grad<GT>;
-        const ADAMA_GLOBAL typename G::Vec *C = global_ptr<typename G::Vec>(d.c, e0 * sizeof(typename G::Elem));
-        typename G::Vec g[U];
-        f32x4 m[U], v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            g[u] = ld<ntg>(C + i);
-            m[u] = ld<ntl>(A + i);
-            v[u] = ld<ntl>(B + i);
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = u * kBlock + tid;
+        f32x4 gf = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (op_has_grad(OpK)) gf = G::widen(g[u]);
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            float e[3] = {x[0][u][j], x[1][u][j], NS == 3 ? x[NS - 1][u][j] : 0.0f};
+            element_op<OpK>(e, gf[j], sc);
+#pragma unroll
+            for (int k = 0; k < NS; ++k) x[k][u][j] = e[k];
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            f32x4 gf = G::widen(g[u]);
-            fold4(m[u], v[u], gf, sc);
-            st<nts>(A + i, m[u]);
-            st<nts>(B + i, v[u]);
-        }
-    } else if constexpr (OpK == kDecay) {
-        f32x4 m[U], v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            m[u] = ld<ntl>(A + i);
-            v[u] = ld<ntl>(B + i);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            decay4(m[u], v[u], sc);
-            st<nts>(A + i, m[u]);
-            st<nts>(B + i, v[u]);
-        }
-    } else {
-        const ADAMA_GLOBAL f32x4 *C = global_ptr<f32x4>(d.c, e0 * 4);
-        f32x4 th[U], m[U], v[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            th[u] = ld<ntl>(A + i);
-            m[u] = ld<ntl>(B + i);
-            v[u] = ld<ntl>(C + i);
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            uint32_t i = u * kBlock + tid;
-            apply4(th[u], m[u], v[u], sc);
-            st<nts>(A + i, th[u]);
-        }
+        for (int k = 0; k < NS; ++k)
+            if ((op_store_mask(OpK) >> k) & 1) st<nts>(S[k] + i, x[k][u]);
     }
 }
 
@@ -305,58 +172,49 @@ __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint3
 template <int OpK, int GT>
 __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t pre, uint64_t coord, const Scalars &sc)
 {
-    int kind = group_kind(vec, pre, d.n, coord);
+    constexpr int NS = op_states(OpK);
+    using G = Grad<GT>;
+    const int kind = group_kind(vec, pre, d.n, coord);
     if (kind == 0) return;
-    ADAMA_GLOBAL float *a = global_ptr<float>(d.a);
-    ADAMA_GLOBAL float *b = global_ptr<float>(d.b);
     if (kind == 2) {
-        uint64_t e = coord - pre;
-        ADAMA_GLOBAL f32x4 *A = global_ptr<f32x4>(d.a, e * 4);
-        ADAMA_GLOBAL f32x4 *B = global_ptr<f32x4>(d.b, e * 4);
-        if constexpr (OpK == kFold) {
-            using G = Grad<GT>;
-            f32x4 gf = G::widen(*global_ptr<typename G::Vec>(d.c, e * sizeof(typename G::Elem)));
-            f32x4 m = *A, v = *B;
-            fold4(m, v, gf, sc);
-            *A = m;
-            *B = v;
-        } else if constexpr (OpK == kDecay) {
-            f32x4 m = *A, v = *B;
-            decay4(m, v, sc);
-            *A = m;
-            *B = v;
-        } else {
-            f32x4 th = *A, m = *B, v = *global_ptr<f32x4>(d.c, e * 4);
-            apply4(th, m, v, sc);
-            *A = th;
+        const uint64_t e = coord - pre;
+        f32x4 x[NS];
+#pragma unroll
+        for (int k = 0; k < NS; ++k) x[k] = *global_ptr<f32x4>(d.s[k], e * 4);
+        f32x4 gf = {0.0f, 0.0f, 0.0f, 0.0f};
+        if constexpr (op_has_grad(OpK)) gf = G::widen(*global_ptr<typename G::Vec>(d.g, e * sizeof(typename G::Elem)));
+#pragma unroll
+        for (int j = 0; j < kGroup; ++j) {
+            float el[3] = {x[0][j], x[1][j], NS == 3 ? x[NS - 1][j] : 0.0f};
+            element_op<OpK>(el, gf[j], sc);
+#pragma unroll
+            for (int k = 0; k < NS; ++k) x[k][j] = el[k];
         }
+#pragma unroll
+        for (int k = 0; k < NS; ++k)
+            if ((op_store_mask(OpK) >> k) & 1) *global_ptr<f32x4>(d.s[k], e * 4) = x[k];
         return;
     }
 #pragma unroll
     for (int j = 0; j < kGroup; ++j) {
-        uint64_t x = coord + j;
-        if (x < pre || x >= pre + d.n) continue;
-        uint64_t e = x - pre;
-        if constexpr (OpK == kFold) {
-            using G = Grad<GT>;
-            float g = G::widen1(global_ptr<typename G::Elem>(d.c)[e]);
-            float m = a[e], v = b[e];
-            fold1(m, v, g, sc);
-            a[e] = m;
-            b[e] = v;
-        } else if constexpr (OpK == kDecay) {
-            float m = a[e], v = b[e];
-            decay1(m, v, sc);
-            a[e] = m;
-            b[e] = v;
-        } else {
-            a[e] = apply1(a[e], b[e], global_ptr<float>(d.c)[e], sc);
-        }
+        const uint64_t xc = coord + j;
+        if (xc < pre || xc >= pre + d.n) continue;
+        const uint64_t e = xc - pre;
+        float el[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int k = 0; k < NS; ++k) el[k] = global_ptr<float>(d.s[k])[e];
+        float g = 0.0f;
+        if constexpr (op_has_grad(OpK)) g = G::widen1(global_ptr<typename G::Elem>(d.g)[e]);
+        element_op<OpK>(el, g, sc);
+#pragma unroll
+        for (int k = 0; k < NS; ++k)
+            if ((op_store_mask(OpK) >> k) & 1) global_ptr<float>(d.s[k])[e] = el[k];
     }
 }
 
-// OpK: Op.  GT: GradType (fold only).  U: 16-byte groups per thread per chunk (chunk = 1024*U elements).
-// NT: cache-policy bits.  Grid: any number of workgroups >= 1; workgroup w takes chunks w, w+grid, ...
+// OpK: Op.  GT: GradType (ops with a gradient).  U: 16-byte groups per thread per chunk (chunk =
+// 1024*U elements).  NT: cache-policy bits.  Grid: any number of workgroups >= 1; workgroup w takes
+// chunks w, w+grid, ...
 //
 // The tensor table stays in the kernel argument block and is read with scalar loads: the chunk number
 // depends on the workgroup id alone, so the search for its tensor and the fetch of the descriptor are
@@ -369,14 +227,14 @@ __global__ void __launch_bounds__(kBlock) multi_tensor_kernel(const Table<kMaxTe
     const uint32_t tid = threadIdx.x;
     const uint32_t count = tab.count;
     constexpr uint32_t chunk = kBlock * kGroup * U;
-    constexpr uint32_t c_bytes = OpK == kDecay ? 0u : (OpK == kApply || GT == kF32) ? 4u : 2u;
+    constexpr uint32_t g_bytes = !op_has_grad(OpK) ? 0u : GT == kF32 ? 4u : 2u;
     const uint32_t total = tab.total;
     for (uint32_t c = blockIdx.x; c < total; c += gridDim.x) {
         const uint32_t k = count > 1 ? find_tensor(tab.chunk_start, count, c) : 0u;
         const Desc d = tab.t[k];
         const uint64_t lc = c - tab.chunk_start[k];
-        const uint32_t pre = misalign_elems(d.a);
-        const bool vec = coaligned(d.a, d.b, d.c, c_bytes);
+        const uint32_t pre = misalign_elems(d.s[0]);
+        const bool vec = coaligned(d, op_states(OpK), g_bytes);
         if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {
             interior_chunk<OpK, GT, U, NT>(d, lc * chunk - pre, tid, sc);
         } else {

@@ -87,6 +87,11 @@ class SimulatedBackward:
             self._fold_lists.append(binding.tensor_list(
                 [(base_m + 4 * self.offset[ti], base_v + 4 * self.offset[ti],
                   gb + self.gbytes * self.grad_offset[ti], self.sizes[ti]) for ti in idx]))
+        self._update_lists = []
+        for idx in self.layers:
+            self._update_lists.append(binding.update_list(
+                [(base_t + 4 * self.offset[ti], base_m + 4 * self.offset[ti], base_v + 4 * self.offset[ti],
+                  gb + self.gbytes * self.grad_offset[ti], self.sizes[ti]) for ti in idx]))
         self._state_list = binding.state_list(
             [(base_t + 4 * o, base_m + 4 * o, base_v + 4 * o, n) for o, n in zip(self.offset, self.sizes)])
 
@@ -124,6 +129,37 @@ class SimulatedBackward:
 
     def fold_layer(self, li: int, N: int, beta1: float, beta2: float) -> None:
         binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+
+    # ---- the same mini-batch with the decay and the update riding along with the edge folds ----
+    def begin_step_fused(self) -> None:
+        """t <- t+1 only: the decay is performed by fold_layer_first in micro-batch 0."""
+        self.t += 1
+
+    def fold_layer_first(self, li: int, N: int, beta1: float, beta2: float) -> None:
+        """Micro-batch 0: decay + fold of layer li in one pass (Alg. 1's one-statement form)."""
+        binding.adama_fold_first_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+
+    def fold_layer_last_apply(self, li: int, N: int, lr: float, eps: float, beta1: float, beta2: float) -> None:
+        """Micro-batch N-1: fold + parameter update of layer li in one pass."""
+        binding.adama_fold_last_apply_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1, beta2,
+                                            self.t, self.stream_handle)
+
+    def mini_batch_fused(self, produce: Callable[[int, int], None], N: int, lr: float, eps: float, beta1: float,
+                         beta2: float) -> None:
+        """One full pass of the hot path with fused edges; bit-identical to mini_batch()."""
+        if N == 1:                       # a single micro-batch is both first and last: keep the decay separate
+            self.begin_step(beta1, beta2)
+        else:
+            self.begin_step_fused()
+        for i in range(N):
+            for li in range(len(self.layers) - 1, -1, -1):
+                produce(i, li)
+                if i == N - 1:
+                    self.fold_layer_last_apply(li, N, lr, eps, beta1, beta2)
+                elif i == 0:
+                    self.fold_layer_first(li, N, beta1, beta2)
+                else:
+                    self.fold_layer(li, N, beta1, beta2)
 
     def micro_batch(self, produce: Callable[[int], None], N: int, beta1: float, beta2: float) -> None:
         """One backward pass: for each layer, last to first, produce(li) must enqueue on self.stream

@@ -76,11 +76,13 @@ def slices_of(n: int, rng: np.random.Generator, full_below: int = 65536, blocks:
 class WorkloadRun:
     """One workload on the GPU (harness) and in the oracle (on all elements or on sampled slices)."""
 
-    def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0"):
+    def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0",
+                 fused: bool = False):
         from paper_2305_19982_amd.harness import SimulatedBackward
 
         self.w = w
         self.sampled = sampled
+        self.fused = fused      # decay inside micro-batch 0's folds, update inside micro-batch N-1's
         self.hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, device=device, pack=pack)
         rng = np.random.default_rng(1234)
         self.slices = [slices_of(t.n, rng) if sampled else [(0, t.n)] for t in w.tensors]
@@ -122,16 +124,26 @@ class WorkloadRun:
 
     def run_step(self, step: int, check_grad_bits: bool = False) -> dict:
         w = self.w
-        self.hb.begin_step(w.beta1, w.beta2)
+        fused = self.fused and w.N > 1
+        if fused:
+            self.hb.begin_step_fused()
+        else:
+            self.hb.begin_step(w.beta1, w.beta2)
         self.ref.begin_step(w.beta1, w.beta2)
         for i in range(w.N):
             for li in w.backward_layers():
                 self.produce(step, i, li)
                 if check_grad_bits:
                     self.assert_grad_bits(step, i, li)
-                self.hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                if self.fused and i == w.N - 1:
+                    self.hb.fold_layer_last_apply(li, w.N, w.lr, w.eps, w.beta1, w.beta2)
+                elif fused and i == 0:
+                    self.hb.fold_layer_first(li, w.N, w.beta1, w.beta2)
+                else:
+                    self.hb.fold_layer(li, w.N, w.beta1, w.beta2)
                 self.oracle_fold_layer(step, i, li)
-        self.hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+        if not self.fused:
+            self.hb.apply(w.lr, w.eps, w.beta1, w.beta2)
         self.ref.apply(w.lr, w.eps, w.beta1, w.beta2)
         assert self.hb.t == self.ref.t == step
         return self.compare()

@@ -112,6 +112,29 @@ def test_apply_rejects_bad_arguments(lib, override, text):
     assert ei.value.status == binding.ERR_INVALID_ARG and text in ei.value.message
 
 
+def test_fused_entry_points_validate_like_their_parts(lib):
+    ok = dict(theta=FAKE, m=FAKE + (1 << 30), v=FAKE + (2 << 30), grad=FAKE + (3 << 30))
+    binding.adama_fold_first(None, None, None, "bf16", 0, 4, 0.9, 0.999)
+    binding.adama_fold_last_apply(None, None, None, None, "f16", 0, 4, 1e-3, 1e-8, 0.9, 0.999, 1)
+    binding.adama_fold_first_multi([], 0, "f32", 2, 0.9, 0.999)
+    binding.adama_fold_last_apply_multi([], 0, "f32", 2, 1e-3, 1e-8, 0.9, 0.999, 5)
+    for bad, text in ((dict(N=0), "micro-batches"), (dict(beta1=1.0), "[0, 1)"), (dict(m=None), "m is NULL"),
+                      (dict(gdt=9), "dtype")):
+        a = dict(ok, gdt=binding.BF16, N=4, beta1=0.9, beta2=0.999)
+        a.update(bad)
+        with pytest.raises(binding.AdamaError) as ei:
+            binding.adama_fold_first(a["m"], a["v"], a["grad"], a["gdt"], 100, a["N"], a["beta1"], a["beta2"])
+        assert text in ei.value.message
+    for bad, text in ((dict(t=0), "t >= 1"), (dict(theta=None), "theta is NULL"), (dict(grad=None), "grad is NULL"),
+                      (dict(eps=-1.0), "eps"), (dict(N=-1), "micro-batches"), (dict(lr=float("nan")), "lr")):
+        a = dict(ok, gdt=binding.F32, N=4, beta1=0.9, beta2=0.999, lr=1e-3, eps=1e-8, t=1)
+        a.update(bad)
+        with pytest.raises(binding.AdamaError) as ei:
+            binding.adama_fold_last_apply(a["theta"], a["m"], a["v"], a["grad"], a["gdt"], 100, a["N"], a["lr"],
+                                          a["eps"], a["beta1"], a["beta2"], a["t"])
+        assert ei.value.status in (binding.ERR_INVALID_ARG,) and text in ei.value.message
+
+
 def test_begin_step_hyper_parameters(lib):
     with pytest.raises(binding.AdamaError):
         binding.adama_begin_step(FAKE, FAKE + 4096, 10, -0.5, 0.999)
@@ -130,9 +153,9 @@ def _walk_and_check(entries, op, gdt):
     touched, nvec, nsc, launches = binding.adama_debug_walk(entries, op, gdt)
     for k, (tch, e) in enumerate(zip(touched, entries)):
         arr = np.frombuffer(tch, dtype=np.uint8)
-        assert arr.size == e[3]
+        assert arr.size == e[4]
         assert np.all(arr == 1), f"tensor {k}: elements touched {np.unique(arr)} times"
-    assert nvec * 4 + nsc == sum(e[3] for e in entries)
+    assert nvec * 4 + nsc == sum(e[4] for e in entries)
     return nvec, nsc, launches
 
 
@@ -143,7 +166,7 @@ def test_geometry_aligned_tensors_use_vector_accesses(lib, gdt, gb):
     entries = []
     a = FAKE
     for n in sizes:
-        entries.append((a, a + (1 << 32), a + (2 << 32), n))
+        entries.append((a + (3 << 32), a, a + (1 << 32), a + (2 << 32), n))
         a += (4 * n + 255) // 256 * 256
     nvec, nsc, launches = _walk_and_check(entries, 1, gdt)
     assert launches == 1
@@ -151,7 +174,8 @@ def test_geometry_aligned_tensors_use_vector_accesses(lib, gdt, gb):
     del rng
 
 
-@pytest.mark.parametrize("op,gdt,gb", [(0, "f32", 4), (1, "f32", 4), (1, "bf16", 2), (1, "f16", 2), (2, "f32", 4)])
+@pytest.mark.parametrize("op,gdt,gb", [(0, "f32", 4), (1, "f32", 4), (1, "bf16", 2), (1, "f16", 2), (2, "f32", 4),
+                                       (3, "bf16", 2), (3, "f32", 4), (4, "f16", 2), (4, "f32", 4)])
 def test_geometry_misaligned_and_large(lib, op, gdt, gb):
     rng = np.random.default_rng(2)
     entries = []
@@ -162,12 +186,13 @@ def test_geometry_misaligned_and_large(lib, op, gdt, gb):
         a = FAKE + (i << 24) + 4 * pre
         b = FAKE + (1 << 36) + (i << 24) + 4 * (pre if co else (pre + 1) % 4)
         c = FAKE + (2 << 36) + (i << 24) + gb * pre
-        entries.append((a, b, c, n))
+        th = FAKE + (6 << 36) + (i << 24) + 4 * (pre if (co or i % 3) else (pre + 2) % 4)
+        entries.append((th, a, b, c, n))
     # one launch big enough for the 4096-element chunks, with every misalignment
     for pre in range(4):
         n = (1 << 22) + 3 * pre + 1
-        entries.append((FAKE + (3 << 36) + (pre << 28) + 4 * pre, FAKE + (4 << 36) + (pre << 28) + 4 * pre,
-                        FAKE + (5 << 36) + (pre << 28) + gb * pre, n))
+        entries.append((FAKE + (7 << 36) + (pre << 28) + 4 * pre, FAKE + (3 << 36) + (pre << 28) + 4 * pre,
+                        FAKE + (4 << 36) + (pre << 28) + 4 * pre, FAKE + (5 << 36) + (pre << 28) + gb * pre, n))
     nvec, nsc, launches = _walk_and_check(entries, op, gdt)
     assert launches == 1 and nvec > 0 and nsc > 0
 
@@ -179,9 +204,11 @@ def test_geometry_many_tensors_split_into_launches(lib):
     a = FAKE
     for i in range(2 * cap + 17):
         n = int(rng.integers(0, 3000))
-        entries.append((a, a + (1 << 32), a + (2 << 32), n))
+        entries.append((a + (3 << 32), a, a + (1 << 32), a + (2 << 32), n))
         a += 4 * n                                   # packed back to back: all misalignments occur
     nvec, nsc, launches = _walk_and_check(entries, 1, "bf16")
+    assert launches == 3
+    nvec, nsc, launches = _walk_and_check(entries, 4, "bf16")
     assert launches == 3
 
 
@@ -196,7 +223,9 @@ def test_geometry_walk_flags_nothing_on_workload_shapes(lib):
             entries, goff = [], 0
             for ti in idx:
                 n = w.tensors[ti].n
-                entries.append((FAKE + 4 * off, FAKE + (1 << 36) + 4 * off, FAKE + (2 << 36) + w.grad_bytes * goff, n))
+                entries.append((FAKE + (3 << 36) + 4 * off, FAKE + 4 * off, FAKE + (1 << 36) + 4 * off,
+                                FAKE + (2 << 36) + w.grad_bytes * goff, n))
                 off += n
                 goff += n
-            _walk_and_check(entries, 1, w.gdtype)
+            for op in (1, 3, 4):
+                _walk_and_check(entries, op, w.gdtype)

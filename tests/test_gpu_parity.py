@@ -253,3 +253,72 @@ def test_reduced_workload_full_parity(torch_cuda, name, pack):
         _log(f"{w.name} [{pack}] step {step}: {stats}")
     assert run.hb.peak_grad_bytes <= (w.largest_layer_elems + 128 * 32) * w.grad_bytes
     assert run.hb.peak_grad_bytes < run.hb.whole_model_grad_bytes
+
+
+# ---------------------------------------------------------------------------
+# fused edge forms: decay inside the first fold, update inside the last fold
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+def test_fused_edges_bitwise_equal_separate_calls(torch_cuda, gdt):
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    rng = np.random.default_rng(8)
+    sizes = [int(x) for x in rng.integers(0, 9000, 100)] + [300001, (1 << 22) + 77, 0, 1, 5]
+    gbytes = synth.gen.DTYPE_BYTES[gdt]
+    total = sum(sizes)
+    names = ("t", "m", "v")
+    a = {k + s: torch.zeros(total + 8, dtype=torch.float32, device="cuda:0") for k in names for s in "12"}
+    g = torch.zeros((total + 8) * gbytes, dtype=torch.uint8, device="cuda:0")
+    synth.fill_device(g.data_ptr(), synth.Spec(key=77, sigma=1e-2, p_zero=0.01, p_outlier=0.001), gdt, total, 0)
+    for s in "12":
+        synth.fill_device(a["t" + s].data_ptr(), synth.Spec(key=1, sigma=0.02), "f32", total, 0)
+        synth.fill_device(a["m" + s].data_ptr(), synth.Spec(key=2, sigma=1e-3), "f32", total, 0)
+        synth.fill_device(a["v" + s].data_ptr(), synth.Spec(key=3, sigma=1e-5), "f32", total, 0)
+        a["v" + s].abs_()
+    fold1, fold2, upd1, st2, off = [], [], [], [], 0
+    for n in sizes:                      # packed back to back: every misalignment occurs
+        p = {k: a[k].data_ptr() + 4 * off for k in a}
+        pg = g.data_ptr() + gbytes * off
+        fold1.append((p["m1"], p["v1"], pg, n))
+        upd1.append((p["t1"], p["m1"], p["v1"], pg, n))
+        fold2.append((p["m2"], p["v2"], pg, n))
+        st2.append((p["t2"], p["m2"], p["v2"], n))
+        off += n
+    N, t = 4, 3
+    # fused: first fold carries the decay, last fold carries the update
+    binding.adama_fold_first_multi(fold1, None, gdt, N, B1, B2)
+    binding.adama_fold_multi(fold1, None, gdt, N, B1, B2)
+    binding.adama_fold_last_apply_multi(upd1, None, gdt, N, LR, EPS, B1, B2, t)
+    # separate calls
+    binding.adama_begin_step_multi(st2, None, B1, B2)
+    binding.adama_fold_multi(fold2, None, gdt, N, B1, B2)
+    binding.adama_fold_multi(fold2, None, gdt, N, B1, B2)
+    binding.adama_fold_multi(fold2, None, gdt, N, B1, B2)
+    binding.adama_apply_multi(st2, None, LR, EPS, B1, B2, t)
+    torch.cuda.synchronize()
+    for k in names:
+        assert torch.equal(a[k + "1"], a[k + "2"]), f"{k}: fused and separate paths differ"
+    # single-tensor forms agree with the list forms
+    b = {k: torch.zeros(70001, dtype=torch.float32, device="cuda:0") for k in ("t1", "m1", "v1", "t2", "m2", "v2")}
+    for s in "12":
+        synth.fill_device(b["t" + s].data_ptr(), synth.Spec(key=4, sigma=0.02), "f32", 70001, 0)
+        synth.fill_device(b["m" + s].data_ptr(), synth.Spec(key=5, sigma=1e-3), "f32", 70001, 0)
+    binding.adama_fold_first(b["m1"], b["v1"], g, gdt, 70001, N, B1, B2)
+    binding.adama_fold_last_apply(b["t1"], b["m1"], b["v1"], g, gdt, 70001, N, LR, EPS, B1, B2, 1)
+    binding.adama_begin_step(b["m2"], b["v2"], 70001, B1, B2)
+    binding.adama_fold(b["m2"], b["v2"], g, gdt, 70001, N, B1, B2)
+    binding.adama_fold(b["m2"], b["v2"], g, gdt, 70001, N, B1, B2)
+    binding.adama_apply(b["t2"], b["m2"], b["v2"], 70001, LR, EPS, B1, B2, 1)
+    torch.cuda.synchronize()
+    for k in names:
+        assert torch.equal(b[k + "1"], b[k + "2"]), f"{k}: single-tensor fused and separate paths differ"
+
+
+@pytest.mark.parametrize("name", ["c1", "c3", "c4"])
+def test_reduced_workload_fused_parity(torch_cuda, name):
+    w = configs.reduced(name)
+    run = WorkloadRun(w, pack="tight", sampled=False, fused=True)
+    for step in range(1, w.steps + 1):
+        stats = run.run_step(step)
+        _log(f"{w.name} [fused] step {step}: {stats}")
