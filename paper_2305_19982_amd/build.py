@@ -11,8 +11,10 @@ SOURCES = [os.path.join(PKG, "csrc", "adama.hip")]
 HEADERS = [os.path.join(PKG, "csrc", "adama_kernels.hpp"), os.path.join(PKG, "csrc", "adama_index.hpp"),
            os.path.join(ROOT, "include", "adama.h")]
 # -ffp-contract=off: the kernels spell out every fused multiply-add they want.
+# -fno-slp-vectorize: every wide access is written as a vector type already; the SLP pass only turns
+# the scalar table search into a long vector-ALU bit-twiddling sequence.
 # Packed-fp32 instructions are disabled on purpose (target feature below).
-HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off",
+HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off", "-fno-slp-vectorize",
                "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
                "-Wall", "-Wno-unused-command-line-argument", "-fPIC", "-shared"]
 

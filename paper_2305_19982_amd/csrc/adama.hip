@@ -39,9 +39,8 @@ constexpr int kUBig = 4;                      // chunk = 4096 elements: 8..12 16
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
 constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long use kUBig
-// One workgroup per chunk: the hardware dispatcher refills a CU as soon as a workgroup retires,
-// which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
-constexpr uint32_t kMaxGrid = 1u << 30;
+// One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
+// a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 
 uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF32 ? 4u : 2u; }
@@ -91,37 +90,39 @@ adama_status for_each_batch(const Desc *descs, int count, Emit &&emit)
 }
 
 template <int OpK, int GT, int U>
-void launch_one(const Batch &b, const Scalars &sc, unsigned grid, hipStream_t stream)
+void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
-    hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, U, kNtPolicy>), dim3(grid), dim3(kBlock), 0, stream, b.tab, sc);
+    if (b.tab.count == 1)
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, U, kNtPolicy, true>), dim3(b.total), dim3(kBlock), 0, stream, b.tab, sc);
+    else
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, U, kNtPolicy, false>), dim3(b.total), dim3(kBlock), 0, stream, b.tab, sc);
 }
 
 template <int OpK, int GT>
-void launch_u(const Batch &b, const Scalars &sc, unsigned grid, hipStream_t stream)
+void launch_u(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
-    if (b.u == kUBig) launch_one<OpK, GT, kUBig>(b, sc, grid, stream);
-    else launch_one<OpK, GT, kUSmall>(b, sc, grid, stream);
+    if (b.u == kUBig) launch_one<OpK, GT, kUBig>(b, sc, stream);
+    else launch_one<OpK, GT, kUSmall>(b, sc, stream);
 }
 
 template <int OpK>
-void launch_gdt(int gdt, const Batch &b, const Scalars &sc, unsigned grid, hipStream_t stream)
+void launch_gdt(int gdt, const Batch &b, const Scalars &sc, hipStream_t stream)
 {
-    if constexpr (!op_has_grad(OpK)) launch_u<OpK, kF32>(b, sc, grid, stream);
-    else if (gdt == kF32) launch_u<OpK, kF32>(b, sc, grid, stream);
-    else if (gdt == kBF16) launch_u<OpK, kBF16>(b, sc, grid, stream);
-    else launch_u<OpK, kF16>(b, sc, grid, stream);
+    if constexpr (!op_has_grad(OpK)) launch_u<OpK, kF32>(b, sc, stream);
+    else if (gdt == kF32) launch_u<OpK, kF32>(b, sc, stream);
+    else if (gdt == kBF16) launch_u<OpK, kBF16>(b, sc, stream);
+    else launch_u<OpK, kF16>(b, sc, stream);
 }
 
 adama_status launch_all(int op, int gdt, const Desc *descs, int count, const Scalars &sc, hipStream_t stream)
 {
     return for_each_batch(descs, count, [&](const Batch &b, int) -> adama_status {
-        const unsigned grid = b.total < kMaxGrid ? b.total : kMaxGrid;
         switch (op) {
-        case kDecay: launch_gdt<kDecay>(gdt, b, sc, grid, stream); break;
-        case kFold: launch_gdt<kFold>(gdt, b, sc, grid, stream); break;
-        case kApply: launch_gdt<kApply>(gdt, b, sc, grid, stream); break;
-        case kFoldFirst: launch_gdt<kFoldFirst>(gdt, b, sc, grid, stream); break;
-        default: launch_gdt<kFoldLastApply>(gdt, b, sc, grid, stream); break;
+        case kDecay: launch_gdt<kDecay>(gdt, b, sc, stream); break;
+        case kFold: launch_gdt<kFold>(gdt, b, sc, stream); break;
+        case kApply: launch_gdt<kApply>(gdt, b, sc, stream); break;
+        case kFoldFirst: launch_gdt<kFoldFirst>(gdt, b, sc, stream); break;
+        default: launch_gdt<kFoldLastApply>(gdt, b, sc, stream); break;
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(ADAMA_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
@@ -394,7 +395,7 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
             const uint32_t cnt = b.tab.count;
             const int base = i0 + first;   // list index of the batch's first tensor
             for (uint32_t c = 0; c < b.total; ++c) {
-                const uint32_t k = cnt > 1 ? find_tensor(b.tab.chunk_start, cnt, c) : 0u;
+                const uint32_t k = cnt > 1 ? find_tensor(b.tab.chunk_start, c) : 0u;
                 const Desc &d = b.tab.t[k];
                 const uint64_t lc = c - b.tab.chunk_start[k];
                 const uint32_t pre = misalign_elems(d.s[0]);

@@ -76,20 +76,24 @@ ADAMA_HD uint64_t chunks_of(uint32_t pre, uint64_t n, uint32_t chunk)
     return n == 0 ? 0 : (pre + n + chunk - 1) / chunk;
 }
 
-// Largest k in [0, count) with start[k] <= c, given start[0] == 0 <= c < start[count].
-// Zero-length tensors (start[k] == start[k+1]) are skipped by the tie rule.
-// start[] is non-decreasing, so k is the number of entries start[1..count-1] that are <= c.  Counting
-// them in blocks of 16 keeps every load independent of the others (one scalar-cache latency for the
-// whole search instead of one per bisection step); entries past `count` must hold 0xFFFFFFFF.
+// Largest k in [0, count) with start[k] <= c, given start[0] == 0 <= c < start[count] and every entry
+// past [count] equal to 0xFFFFFFFF.  Zero-length tensors (start[k] == start[k+1]) are skipped by the
+// tie rule.  start[] is non-decreasing, so k is the number of entries start[1..] that are <= c.
+// They are counted in blocks of 16 whose loads do not depend on one another (one scalar-cache latency
+// per block instead of one per bisection step); a block with fewer than 16 hits ends the search, so
+// the tensor count itself is never read.
 template <typename StartArray>
-ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t count, uint32_t c)
+ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t c)
 {
     uint32_t k = 0;
-    for (uint32_t base = 0; base < count; base += 16) {
+    for (uint32_t base = 0;; base += 16) {
+        uint32_t hits = 0;
 #if defined(__HIPCC__)
 #pragma unroll
 #endif
-        for (uint32_t j = 0; j < 16; ++j) k += (start[base + j + 1] <= c) ? 1u : 0u;
+        for (uint32_t j = 0; j < 16; ++j) hits += (start[base + j + 1] <= c) ? 1u : 0u;
+        k += hits;
+        if (hits < 16) break;
     }
     return k;
 }

@@ -213,35 +213,33 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
 }
 
 // OpK: Op.  GT: GradType (ops with a gradient).  U: 16-byte groups per thread per chunk (chunk =
-// 1024*U elements).  NT: cache-policy bits.  Grid: any number of workgroups >= 1; workgroup w takes
-// chunks w, w+grid, ...
+// 1024*U elements).  NT: cache-policy bits.  SINGLE: the launch holds exactly one tensor.
+// Launch contract: gridDim.x == tab.total, one workgroup per chunk.
 //
 // The tensor table stays in the kernel argument block and is read with scalar loads: the chunk number
-// depends on the workgroup id alone, so the search for its tensor and the fetch of the descriptor are
-// wave-uniform and are served by the scalar cache.  (Staging the table in LDS first was measured and
-// dropped: in a kernel that saturates the vector memory path, the vector loads that would fill LDS
-// queue behind the streaming traffic and delay every workgroup's first data load by microseconds.)
-template <int OpK, int GT, int U, int NT>
+// is the workgroup id, so the search for its tensor and the fetch of the descriptor are wave-uniform
+// and are served by the scalar cache.  Nothing the first data load depends on takes more than two
+// scalar-load round trips (one for a single-tensor launch).  (Staging the table in LDS first was
+// measured and dropped: in a kernel that saturates the vector memory path, the vector loads that
+// would fill LDS queue behind the streaming traffic and delay every workgroup's first data load.)
+template <int OpK, int GT, int U, int NT, bool SINGLE>
 __global__ void __launch_bounds__(kBlock) multi_tensor_kernel(const Table<kMaxTensors> tab, const Scalars sc)
 {
     const uint32_t tid = threadIdx.x;
-    const uint32_t count = tab.count;
+    const uint32_t c = blockIdx.x;
     constexpr uint32_t chunk = kBlock * kGroup * U;
     constexpr uint32_t g_bytes = !op_has_grad(OpK) ? 0u : GT == kF32 ? 4u : 2u;
-    const uint32_t total = tab.total;
-    for (uint32_t c = blockIdx.x; c < total; c += gridDim.x) {
-        const uint32_t k = count > 1 ? find_tensor(tab.chunk_start, count, c) : 0u;
-        const Desc d = tab.t[k];
-        const uint64_t lc = c - tab.chunk_start[k];
-        const uint32_t pre = misalign_elems(d.s[0]);
-        const bool vec = coaligned(d, op_states(OpK), g_bytes);
-        if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {
-            interior_chunk<OpK, GT, U, NT>(d, lc * chunk - pre, tid, sc);
-        } else {
+    const uint32_t k = SINGLE ? 0u : find_tensor(tab.chunk_start, c);
+    const Desc d = tab.t[k];
+    const uint64_t lc = SINGLE ? c : c - tab.chunk_start[k];
+    const uint32_t pre = misalign_elems(d.s[0]);
+    const bool vec = coaligned(d, op_states(OpK), g_bytes);
+    if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {
+        interior_chunk<OpK, GT, U, NT>(d, lc * chunk - pre, tid, sc);
+    } else {
 #pragma unroll 1
-            for (int u = 0; u < U; ++u)
-                boundary_group<OpK, GT>(d, vec, pre, lc * chunk + (uint64_t)(u * kBlock + tid) * kGroup, sc);
-        }
+        for (int u = 0; u < U; ++u)
+            boundary_group<OpK, GT>(d, vec, pre, lc * chunk + (uint64_t)(u * kBlock + tid) * kGroup, sc);
     }
 }
 
