@@ -1,0 +1,133 @@
+"""AdamA on a real PyTorch backward pass (paper Sec. 3.3, single-device scenario).
+
+The paper inserts the optimizer-state accumulation and the gradient release into the backward pass
+with hooks.  This module does the same on PyTorch-ROCm, with libadama doing all of the optimizer
+arithmetic: a post-accumulate-grad hook on every parameter counts down its layer; when the last
+gradient of a layer has been produced, ONE adama_fold_multi launch folds the whole layer's gradients
+into m and v on the stream autograd is running on, and the gradients are released at once
+(`p.grad = None` hands the memory back to the caching allocator, which reuses it for the next layer).
+Peak gradient memory is therefore about one layer instead of the whole model.
+
+PyTorch is the producer of gradients and the owner of memory here; theta is the parameters'
+own float32 storage, m and v are allocated by this class.  Gradients may be float32, bfloat16 or
+float16 (the dtype autograd produces for the parameter); parameters must be float32.
+"""
+from __future__ import annotations
+
+from typing import Iterable, Sequence
+
+import torch
+
+from . import binding
+
+_GDT = {torch.float32: "f32", torch.bfloat16: "bf16", torch.float16: "f16"}
+
+
+def leaf_layers(module: torch.nn.Module) -> list:
+    """Default layer grouping: every module that directly owns parameters is one layer."""
+    layers = []
+    for sub in module.modules():
+        ps = [p for p in sub.parameters(recurse=False) if p.requires_grad]
+        if ps:
+            layers.append(ps)
+    return layers
+
+
+class AdamAccumulation:
+    """Adam Accumulation driven by backward hooks.
+
+    layers : groups of parameters folded by one launch each (e.g. leaf_layers(model), or one group per
+             transformer block); every trainable parameter must appear in exactly one group
+    N      : micro-batches per mini-batch; the loss of each micro-batch is NOT divided by N by the caller
+             (the fold applies 1/N, as in Alg. 2)
+
+    Per mini-batch:  begin_mini_batch();  N x (forward; loss.backward());  step()
+    """
+
+    def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-3,
+                 betas: tuple = (0.9, 0.999), eps: float = 1e-8, N: int = 1, fused_edges: bool = True):
+        binding.load()
+        self.lr, self.beta1, self.beta2, self.eps, self.N = float(lr), float(betas[0]), float(betas[1]), float(eps), int(N)
+        self.fused_edges = bool(fused_edges) and self.N > 1
+        self.t = 0
+        self.micro = 0
+        self.layers = [list(ps) for ps in layers]
+        self.m, self.v = {}, {}
+        self._layer_of = {}
+        self._pending = []
+        self._handles = []
+        self.peak_live_grad_bytes = 0
+        self._live_grad_bytes = 0
+        seen = set()
+        for li, ps in enumerate(self.layers):
+            for p in ps:
+                if id(p) in seen:
+                    raise ValueError("a parameter appears in two layers")
+                seen.add(id(p))
+                if p.dtype != torch.float32 or not p.is_cuda or not p.is_contiguous():
+                    raise ValueError("parameters must be contiguous float32 CUDA tensors")
+                self.m[p] = torch.zeros_like(p)
+                self.v[p] = torch.zeros_like(p)
+                self._layer_of[p] = li
+                self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
+            self._pending.append(len(ps))
+        self._state_list = binding.state_list(
+            [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel()) for ps in self.layers for p in ps])
+
+    # ---- Alg. 2 ----
+    def begin_mini_batch(self) -> None:
+        """t <- t+1 and the moment decay (deferred into the first micro-batch's folds when fused)."""
+        self.t += 1
+        self.micro = 0
+        if not self.fused_edges:
+            binding.adama_begin_step_multi(self._state_list, None, self.beta1, self.beta2,
+                                           torch.cuda.current_stream().cuda_stream)
+
+    def _on_grad(self, p: torch.nn.Parameter) -> None:
+        li = self._layer_of[p]
+        self._live_grad_bytes += p.grad.numel() * p.grad.element_size()
+        self.peak_live_grad_bytes = max(self.peak_live_grad_bytes, self._live_grad_bytes)
+        self._pending[li] -= 1
+        if self._pending[li] == 0:
+            self._fold_layer(li)
+
+    def _fold_layer(self, li: int) -> None:
+        ps = self.layers[li]
+        grads = [p.grad if p.grad.is_contiguous() else p.grad.contiguous() for p in ps]
+        gdt = _GDT[grads[0].dtype]
+        if any(g.dtype != grads[0].dtype for g in grads):
+            raise ValueError("gradients of one layer must share a dtype")
+        stream = torch.cuda.current_stream().cuda_stream
+        first = self.fused_edges and self.micro == 0
+        last = self.fused_edges and self.micro == self.N - 1
+        if last:
+            binding.adama_fold_last_apply_multi(
+                [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel())
+                 for p, g in zip(ps, grads)], None, gdt, self.N, self.lr, self.eps, self.beta1, self.beta2, self.t, stream)
+        else:
+            entries = [(self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
+            fn = binding.adama_fold_first_multi if first else binding.adama_fold_multi
+            fn(entries, None, gdt, self.N, self.beta1, self.beta2, stream)
+        for p in ps:                                   # release: the fold is queued on the producing stream
+            self._live_grad_bytes -= p.grad.numel() * p.grad.element_size()
+            p.grad = None
+        self._pending[li] = len(ps)
+
+    def micro_batch_done(self) -> None:
+        """Call after each loss.backward()."""
+        if any(k != len(ps) for k, ps in zip(self._pending, self.layers)):
+            raise RuntimeError("a layer received only part of its gradients in this backward pass")
+        self.micro += 1
+
+    def step(self) -> None:
+        """The bias-corrected update (already done by the last micro-batch's folds when fused)."""
+        if self.micro != self.N:
+            raise RuntimeError(f"step() after {self.micro} of {self.N} micro-batches")
+        if not self.fused_edges:
+            binding.adama_apply_multi(self._state_list, None, self.lr, self.eps, self.beta1, self.beta2, self.t,
+                                      torch.cuda.current_stream().cuda_stream)
+
+    def remove_hooks(self) -> None:
+        for h in self._handles:
+            h.remove()
+        self._handles = []

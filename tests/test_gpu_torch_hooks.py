@@ -1,0 +1,127 @@
+"""AdamA attached to a real PyTorch backward pass through hooks (the paper's single-device system
+design): parameters after a mini-batch match the fp64 oracle fed with the very gradients autograd
+produced, and at most one layer's gradients are alive at any time."""
+import copy
+
+import numpy as np
+import pytest
+
+import oracle
+from parity import check_close
+
+pytestmark = pytest.mark.gpu
+
+
+def _model(torch):
+    torch.manual_seed(0)
+    nn = torch.nn
+    return nn.Sequential(nn.Linear(131, 517), nn.GELU(), nn.LayerNorm(517), nn.Linear(517, 389), nn.GELU(),
+                         nn.Linear(389, 389), nn.LayerNorm(389), nn.Linear(389, 67)).cuda()
+
+
+def _batches(torch, n_micro, steps):
+    g = torch.Generator(device="cuda").manual_seed(1)
+    return [[(torch.randn(32, 131, device="cuda", generator=g), torch.randn(32, 67, device="cuda", generator=g))
+             for _ in range(n_micro)] for _ in range(steps)]
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_hooks_match_oracle_and_release_gradients(fused):
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import AdamAccumulation, leaf_layers
+
+    torch.backends.cuda.matmul.allow_tf32 = False
+    N, steps, lr, b1, b2, eps = 4, 2, 1e-3, 0.9, 0.999, 1e-8
+    ref_model = _model(torch)
+    model = copy.deepcopy(ref_model)
+    data = _batches(torch, N, steps)
+    loss_fn = torch.nn.MSELoss()
+
+    layers = leaf_layers(model)
+    opt = AdamAccumulation(layers, lr=lr, betas=(b1, b2), eps=eps, N=N, fused_edges=fused)
+    ref_params = list(ref_model.parameters())
+    params = [p for ps in layers for p in ps]
+    assert len(params) == len(ref_params)
+    ref = oracle.OracleState([p.detach().cpu().numpy() for p in ref_params])
+    prev_gpu = [p.detach().cpu().numpy().ravel().copy() for p in params]
+    prev_ref = [x.copy() for x in ref.theta]
+    largest_layer = max(sum(p.numel() * 4 for p in ps) for ps in layers)
+    total = sum(p.numel() * 4 for p in params)
+    for step in range(steps):
+        # reference gradients: plain autograd on a twin model holding the same parameter values
+        with torch.no_grad():
+            for rp, p in zip(ref_params, params):
+                rp.copy_(p)
+        ref.begin_step(b1, b2)
+        opt.begin_mini_batch()
+        for (x, y) in data[step]:
+            ref_model.zero_grad(set_to_none=True)
+            loss_fn(ref_model(x), y).backward()
+            for i, rp in enumerate(ref_params):
+                ref.fold(i, rp.grad.detach().cpu().numpy().ravel(), N, b1, b2)
+            loss_fn(model(x), y).backward()
+            opt.micro_batch_done()
+            assert all(p.grad is None for p in params), "gradients must be released inside the backward pass"
+        opt.step()
+        ref.apply(lr, eps, b1, b2)
+        torch.cuda.synchronize()
+        for i, p in enumerate(params):
+            name = f"hooks fused={fused} step {step + 1} param {i}"
+            th = p.detach().cpu().numpy().ravel()
+            if step == 0:
+                # same parameters => same gradients: full parity against the oracle
+                check_close(name, "m", opt.m[p].cpu().numpy().ravel(), ref.m[i])
+                check_close(name, "v", opt.v[p].cpu().numpy().ravel(), ref.v[i])
+                check_close(name, "theta", th, ref.theta[i], prev_gpu[i], prev_ref[i])
+            else:
+                # the oracle's gradients came from the GPU-updated parameters, its own theta differs by rounding
+                assert np.max(np.abs(th - ref.theta[i])) <= 1e-6 + 1e-5 * np.max(np.abs(ref.theta[i]))
+            prev_gpu[i], prev_ref[i] = th.copy(), ref.theta[i].copy()
+            ref.theta[i][:] = th            # keep the twin and the oracle on the GPU trajectory
+    assert opt.peak_live_grad_bytes <= largest_layer
+    assert opt.peak_live_grad_bytes < total / 2
+    opt.remove_hooks()
+
+
+def test_hook_path_peak_memory_below_gradient_accumulation():
+    """Peak allocated memory of a backward pass: whole-model gradients (accumulation) vs one layer (AdamA)."""
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import AdamAccumulation
+
+    def build():
+        torch.manual_seed(0)
+        return torch.nn.Sequential(*[torch.nn.Linear(2048, 2048) for _ in range(24)]).cuda()
+
+    x = torch.randn(8, 2048, device="cuda")
+    grad_bytes = 24 * (2048 * 2048 + 2048) * 4
+
+    model = build()
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    for _ in range(2):
+        model(x).sum().backward()             # plain accumulation into p.grad
+    torch.cuda.synchronize()
+    peak_accum = torch.cuda.max_memory_allocated() - base
+    del model
+    torch.cuda.empty_cache()
+
+    model = build()
+    opt = AdamAccumulation([list(l.parameters()) for l in model], N=2)
+    torch.cuda.synchronize()
+    torch.cuda.reset_peak_memory_stats()
+    base = torch.cuda.memory_allocated()
+    opt.begin_mini_batch()
+    for _ in range(2):
+        model(x).sum().backward()
+        opt.micro_batch_done()
+    opt.step()
+    torch.cuda.synchronize()
+    peak_adama = torch.cuda.max_memory_allocated() - base
+    print(f"peak extra memory during backward: accumulation {peak_accum / 2**20:.1f} MiB, AdamA hooks "
+          f"{peak_adama / 2**20:.1f} MiB (whole-model gradients {grad_bytes / 2**20:.1f} MiB)", flush=True)
+    assert peak_accum >= grad_bytes
+    assert peak_adama < 0.15 * grad_bytes
+    opt.remove_hooks()
