@@ -143,6 +143,17 @@ adama_status adama_apply(float *theta, const float *m, const float *v, size_t n,
 adama_status adama_apply_multi(const adama_state *list, int count, double lr, double eps, double beta1,
                                double beta2, long long t, hipStream_t stream);
 
+/* The update of the data-parallel scheme of Sec. 3.3 (text after Eq. 5): every device has decayed v by
+ * M*beta2 (adama_begin_step accepts that), folded its own micro-batches, and m and v have been summed
+ * over the M devices by an all-reduce, which is the caller's (e.g. RCCL); this call then forms
+ *     m[k] <- m[k] * m_scale,  v[k] <- v[k] * v_scale        (m_scale = 1/M, v_scale = 1/M^2)
+ * writes both back (they are the next mini-batch's starting moments) and applies the Update of Alg. 2
+ * with them.  m_scale, v_scale finite and >= 0; other arguments as adama_apply.  24 B per parameter. */
+adama_status adama_rescale_apply(float *theta, float *m, float *v, size_t n, double m_scale, double v_scale,
+                                 double lr, double eps, double beta1, double beta2, long long t, hipStream_t stream);
+adama_status adama_rescale_apply_multi(const adama_state *list, int count, double m_scale, double v_scale, double lr,
+                                       double eps, double beta1, double beta2, long long t, hipStream_t stream);
+
 /* Message of the last failing call on this thread ("" if none).  Valid until the next call
  * on the same thread. */
 const char *adama_last_error(void);
@@ -162,7 +173,8 @@ void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems
  * (launch, chunk, thread, access) the kernels would issue for `list` and adds 1 to touched[k][e]
  * for each element e of tensor k an access covers (touched[k] is a host array of list[k].n bytes,
  * zero-filled by the caller).  op: 0 decay (m, v), 1 fold (m, v, grad), 2 apply (theta, m, v),
- * 3 fold_first (m, v, grad), 4 fold_last_apply (theta, m, v, grad); fields an op does not use are
+ * 3 fold_first (m, v, grad), 4 fold_last_apply (theta, m, v, grad), 5 rescale_apply (theta, m, v);
+ * fields an op does not use are
  * ignored.  *vector_accesses and *scalar_accesses count 16-byte and single-element accesses.
  * Returns ADAMA_ERR_INVALID_ARG if an access would leave a tensor or a vector access would be
  * misaligned.  Used by the CPU test-suite.

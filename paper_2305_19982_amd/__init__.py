@@ -17,4 +17,6 @@ from .binding import (  # noqa: F401
     adama_fold_multi,
     adama_last_error,
     adama_max_tensors_per_launch,
+    adama_rescale_apply,
+    adama_rescale_apply_multi,
 )

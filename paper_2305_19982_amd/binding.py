@@ -71,12 +71,15 @@ def load() -> ctypes.CDLL:
                                                 dbl, i64, vp]
     lib.adama_apply.argtypes = [vp, vp, vp, sz, dbl, dbl, dbl, dbl, i64, vp]
     lib.adama_apply_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adama_rescale_apply.argtypes = [vp, vp, vp, sz, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
+    lib.adama_rescale_apply_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, dbl, dbl, i64, vp]
     lib.adama_debug_walk.argtypes = [ctypes.POINTER(adama_update_tensor), i32, i32, i32, ctypes.POINTER(vp),
                                      ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_ulonglong),
                                      ctypes.POINTER(i32)]
     for name in ("adama_begin_step", "adama_begin_step_multi", "adama_fold", "adama_fold_multi", "adama_apply",
                  "adama_apply_multi", "adama_fold_first", "adama_fold_first_multi", "adama_fold_last_apply",
-                 "adama_fold_last_apply_multi", "adama_debug_walk"):
+                 "adama_fold_last_apply_multi", "adama_rescale_apply", "adama_rescale_apply_multi",
+                 "adama_debug_walk"):
         getattr(lib, name).restype = i32
     lib.adama_last_error.restype = ctypes.c_char_p
     lib.adama_last_error.argtypes = []
@@ -196,6 +199,20 @@ def adama_apply_multi(lst, count: int | None, lr: float, eps: float, beta1: floa
     if not isinstance(lst, ctypes.Array):
         lst = state_list(lst)
     _check(load().adama_apply_multi(lst, len(lst) if count is None else count, lr, eps, beta1, beta2, t, stream))
+
+
+def adama_rescale_apply(theta, m, v, n: int, m_scale: float, v_scale: float, lr: float, eps: float, beta1: float,
+                        beta2: float, t: int, stream: int = 0) -> None:
+    _check(load().adama_rescale_apply(_ptr(theta), _ptr(m), _ptr(v), n, m_scale, v_scale, lr, eps, beta1, beta2, t,
+                                      stream))
+
+
+def adama_rescale_apply_multi(lst, count: int | None, m_scale: float, v_scale: float, lr: float, eps: float,
+                              beta1: float, beta2: float, t: int, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = state_list(lst)
+    _check(load().adama_rescale_apply_multi(lst, len(lst) if count is None else count, m_scale, v_scale, lr, eps,
+                                            beta1, beta2, t, stream))
 
 
 def adama_debug_walk(entries, op: int, gdt):

@@ -122,6 +122,7 @@ adama_status launch_all(int op, int gdt, const Desc *descs, int count, const Sca
         case kFold: launch_gdt<kFold>(gdt, b, sc, stream); break;
         case kApply: launch_gdt<kApply>(gdt, b, sc, stream); break;
         case kFoldFirst: launch_gdt<kFoldFirst>(gdt, b, sc, stream); break;
+        case kRescaleApply: launch_gdt<kRescaleApply>(gdt, b, sc, stream); break;
         default: launch_gdt<kFoldLastApply>(gdt, b, sc, stream); break;
         }
         hipError_t e = hipGetLastError();
@@ -365,6 +366,27 @@ adama_status adama_apply_multi(const adama_state *list, int count, double lr, do
     set_apply_scalars(sc, lr, eps, beta1, beta2, t);
     return run_list(kApply, kF32, list, count, sc, stream,
                     [](const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; });
+}
+
+adama_status adama_rescale_apply_multi(const adama_state *list, int count, double m_scale, double v_scale, double lr,
+                                       double eps, double beta1, double beta2, long long t, hipStream_t stream)
+{
+    ADAMA_TRY(check_state_args(list, count, true));
+    ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
+    if (!finite_nonneg(m_scale) || !finite_nonneg(v_scale))
+        return fail(ADAMA_ERR_INVALID_ARG, "m_scale = %g, v_scale = %g must be finite and >= 0", m_scale, v_scale);
+    Scalars sc{};
+    set_decay_scalars(sc, m_scale, v_scale);
+    set_apply_scalars(sc, lr, eps, beta1, beta2, t);
+    return run_list(kRescaleApply, kF32, list, count, sc, stream,
+                    [](const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; });
+}
+
+adama_status adama_rescale_apply(float *theta, float *m, float *v, size_t n, double m_scale, double v_scale,
+                                 double lr, double eps, double beta1, double beta2, long long t, hipStream_t stream)
+{
+    adama_state one{theta, m, v, n};
+    return adama_rescale_apply_multi(&one, 1, m_scale, v_scale, lr, eps, beta1, beta2, t, stream);
 }
 
 adama_status adama_apply(float *theta, const float *m, const float *v, size_t n, double lr, double eps,

@@ -27,16 +27,17 @@ constexpr int kGroup = 4;         // elements per 16-byte float32 access
 constexpr int kMaxTensors = 80;   // descriptors per launch (table lives in the kernel argument block)
 
 // The steps of the path.  "First" folds perform the mini-batch's decay on the way (micro-batch 0),
-// "LastApply" folds perform the parameter update on the way (micro-batch N-1).
-enum Op : int { kDecay = 0, kFold = 1, kApply = 2, kFoldFirst = 3, kFoldLastApply = 4, kNumOps = 5 };
+// "LastApply" folds perform the parameter update on the way (micro-batch N-1).  "RescaleApply" is the
+// update of the data-parallel scheme: the all-reduced moments are rescaled, written back, and used.
+enum Op : int { kDecay = 0, kFold = 1, kApply = 2, kFoldFirst = 3, kFoldLastApply = 4, kRescaleApply = 5, kNumOps = 6 };
 
 // Number of float32 state arrays an op touches, and whether it reads a gradient.
 //   decay, fold, fold_first : s = {m, v}
-//   apply, fold_last_apply  : s = {theta, m, v}
-ADAMA_HD constexpr int op_states(int op) { return (op == kApply || op == kFoldLastApply) ? 3 : 2; }
+//   apply, fold_last_apply, rescale_apply : s = {theta, m, v}
+ADAMA_HD constexpr int op_states(int op) { return (op == kApply || op == kFoldLastApply || op == kRescaleApply) ? 3 : 2; }
 ADAMA_HD constexpr bool op_has_grad(int op) { return op == kFold || op == kFoldFirst || op == kFoldLastApply; }
 // Bit k set: state array k is written back.
-ADAMA_HD constexpr int op_store_mask(int op) { return op == kApply ? 1 : op == kFoldLastApply ? 7 : 3; }
+ADAMA_HD constexpr int op_store_mask(int op) { return op == kApply ? 1 : (op == kFoldLastApply || op == kRescaleApply) ? 7 : 3; }
 
 // The arrays of one tensor: up to three float32 state arrays and the gradient.
 struct Desc {

@@ -11,6 +11,7 @@
 //   apply           : read theta, m, v          write theta         16
 //   fold_first      : as fold (the decay rides along)               16 + sizeof(grad)
 //   fold_last_apply : read grad, theta, m, v    write theta, m, v   24 + sizeof(grad)
+//   rescale_apply   : read theta, m, v          write theta, m, v   24
 //
 // so the design goal is HBM bandwidth, not arithmetic: no MFMA, no LDS tiling of
 // data (there is no reuse), only wide coalesced accesses and enough of them in
@@ -50,8 +51,8 @@ enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4 };
 
 // Per-launch scalars, already rounded to float32 from double on the host.
 //   c1 = (1-beta1)/N, c2 = (1-beta2)/N^2            fold, fold_first, fold_last_apply
-//   d1 = beta1, d2 = beta2                           decay, fold_first
-//   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply
+//   d1 = beta1, d2 = beta2                           decay, fold_first (rescale_apply: 1/M, 1/M^2)
+//   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply, rescale_apply
 struct Scalars {
     float c1, c2, d1, d2, step, rs2, eps;
 };
@@ -112,11 +113,12 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 //                                             g*g is exact in float32 for bf16 and fp16 inputs)
 //   apply  (Alg. 2, Update):                  theta <- theta - step*m / (sqrt(v)*rs2 + eps)
 //                                             = theta - lr*m_hat/(sqrt(v_hat)+eps); IEEE sqrt and divide
+//   rescale_apply (Sec. 3.3, after Eq. 5):    m <- m/M, v <- v/M^2 on the all-reduced sums, then apply
 template <int OpK>
 __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars &sc)
 {
     constexpr int im = op_states(OpK) == 3 ? 1 : 0, iv = im + 1;
-    if constexpr (OpK == kDecay || OpK == kFoldFirst) {
+    if constexpr (OpK == kDecay || OpK == kFoldFirst || OpK == kRescaleApply) {
         s[im] = sc.d1 * s[im];
         s[iv] = sc.d2 * s[iv];
     }
@@ -124,7 +126,7 @@ __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars
         s[im] = __builtin_fmaf(sc.c1, g, s[im]);
         s[iv] = __builtin_fmaf(sc.c2, g * g, s[iv]);
     }
-    if constexpr (OpK == kApply || OpK == kFoldLastApply) {
+    if constexpr (OpK == kApply || OpK == kFoldLastApply || OpK == kRescaleApply) {
         const float denom = __builtin_fmaf(__builtin_sqrtf(s[iv]), sc.rs2, sc.eps);
         s[0] = s[0] - (sc.step * s[im]) / denom;
     }

@@ -135,6 +135,18 @@ def test_fused_entry_points_validate_like_their_parts(lib):
         assert ei.value.status in (binding.ERR_INVALID_ARG,) and text in ei.value.message
 
 
+def test_rescale_apply_validation(lib):
+    binding.adama_rescale_apply(None, None, None, 0, 0.5, 0.25, 1e-3, 1e-8, 0.9, 0.999, 1)
+    for bad, text in ((dict(m_scale=-1.0), "m_scale"), (dict(v_scale=float("inf")), "v_scale"), (dict(t=0), "t >= 1"),
+                      (dict(theta=None), "theta is NULL")):
+        a = dict(theta=FAKE, m=FAKE + (1 << 30), v=FAKE + (2 << 30), m_scale=0.5, v_scale=0.25, t=1)
+        a.update(bad)
+        with pytest.raises(binding.AdamaError) as ei:
+            binding.adama_rescale_apply(a["theta"], a["m"], a["v"], 100, a["m_scale"], a["v_scale"], 1e-3, 1e-8, 0.9,
+                                        0.999, a["t"])
+        assert text in ei.value.message
+
+
 def test_begin_step_hyper_parameters(lib):
     with pytest.raises(binding.AdamaError):
         binding.adama_begin_step(FAKE, FAKE + 4096, 10, -0.5, 0.999)
@@ -175,7 +187,7 @@ def test_geometry_aligned_tensors_use_vector_accesses(lib, gdt, gb):
 
 
 @pytest.mark.parametrize("op,gdt,gb", [(0, "f32", 4), (1, "f32", 4), (1, "bf16", 2), (1, "f16", 2), (2, "f32", 4),
-                                       (3, "bf16", 2), (3, "f32", 4), (4, "f16", 2), (4, "f32", 4)])
+                                       (3, "bf16", 2), (3, "f32", 4), (4, "f16", 2), (4, "f32", 4), (5, "f32", 4)])
 def test_geometry_misaligned_and_large(lib, op, gdt, gb):
     rng = np.random.default_rng(2)
     entries = []

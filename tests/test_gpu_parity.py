@@ -322,3 +322,59 @@ def test_reduced_workload_fused_parity(torch_cuda, name):
     for step in range(1, w.steps + 1):
         stats = run.run_step(step)
         _log(f"{w.name} [fused] step {step}: {stats}")
+
+
+# ---------------------------------------------------------------------------
+# Sec. 3.3: M simulated devices on one GPU == one device with N*M micro-batches
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("M,N", [(2, 4), (4, 2), (3, 3)])
+def test_data_parallel_state_sync_arithmetic(torch_cuda, M, N):
+    """Each simulated device decays v by M*beta2 and folds its own N micro-batches with 1/N; the summed
+    states (a torch add stands in for the all-reduce) go through adama_rescale_apply(1/M, 1/M^2).  The
+    result must match the oracle's multi-device combine AND the oracle's single-device N*M run."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n, T, gdt = 100003, 2, "bf16"
+    theta0 = synth.fill_host(synth.Spec(key=41, sigma=0.02), "f32", n)
+    theta = torch.from_numpy(theta0).cuda()
+    m_sync = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v_sync = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    g = torch.zeros(n * 2, dtype=torch.uint8, device="cuda:0")
+    single = oracle.OracleState([theta0])                  # one device, N*M micro-batches
+    ddp_theta = theta0.astype(np.float64)
+    ddp_m, ddp_v = np.zeros(n), np.zeros(n)
+    prev_gpu, prev_ref = theta0.copy(), theta0.astype(np.float64)
+    for t in range(1, T + 1):
+        single.begin_step(B1, B2)
+        m_r = np.repeat(ddp_m[None, :], M, axis=0)
+        v_r = np.repeat(ddp_v[None, :], M, axis=0)
+        m_sum = torch.zeros_like(m_sync)
+        v_sum = torch.zeros_like(v_sync)
+        for r in range(M):
+            m_dev, v_dev = m_sync.clone(), v_sync.clone()
+            binding.adama_begin_step(m_dev, v_dev, n, B1, M * B2)
+            oracle.begin_step(m_r[r], v_r[r], B1, M * B2)
+            for i in range(N):
+                spec = synth.Spec(key=synth.stream_key(43, t, r, i), sigma=3e-3, p_outlier=1e-3)
+                synth.fill_device(g.data_ptr(), spec, gdt, n, 0)
+                binding.adama_fold(m_dev, v_dev, g, gdt, n, N, B1, B2)
+                host = synth.fill_host(spec, gdt, n)
+                oracle.fold(m_r[r], v_r[r], host, N, B1, B2, gdtype=gdt)
+                single.fold(0, host, N * M, B1, B2, gdtype=gdt)
+            m_sum += m_dev                                   # stand-in for the all-reduce (sum)
+            v_sum += v_dev
+        binding.adama_rescale_apply(theta, m_sum, v_sum, n, 1.0 / M, 1.0 / (M * M), LR, EPS, B1, B2, t)
+        m_sync, v_sync = m_sum, v_sum
+        ddp_m, ddp_v = oracle.ddp_combine(m_r, v_r)
+        oracle.apply(ddp_theta, ddp_m, ddp_v, LR, EPS, B1, B2, t)
+        single.apply(LR, EPS, B1, B2)
+        torch.cuda.synchronize()
+        th = theta.cpu().numpy()
+        for label, rm, rv, rt in (("vs oracle combine", ddp_m, ddp_v, ddp_theta),
+                                  ("vs single device N*M", single.m[0], single.v[0], single.theta[0])):
+            name = f"ddp M={M} N={N} t={t} {label}"
+            check_close(name, "m", m_sync.cpu().numpy(), rm)
+            check_close(name, "v", v_sync.cpu().numpy(), rv)
+            check_close(name, "theta", th, rt, prev_gpu, prev_ref)
+        prev_gpu, prev_ref = th.copy(), ddp_theta.copy()
