@@ -74,6 +74,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (the known-size reference for hardware traffic counters)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time one micro-batch's fold sweep as eager launches and as a HIP graph replay")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -164,6 +166,27 @@ def main() -> int:
                 else:
                     hb.fold_layer(li, w.N, w.beta1, w.beta2)
 
+    # ---- launch-bound workloads: one micro-batch's fold sweep as a HIP graph ----
+    graph_sweep = None
+    if args.graph:
+        def sweep() -> None:
+            for li in w.backward_layers():
+                hb.fold_layer(li, w.N, w.beta1, w.beta2)
+
+        g = hb.capture(sweep)
+        reps = 20
+        for fn, label in ((lambda: sweep(), "eager"), (lambda: g.replay(), "graph")):
+            with torch.cuda.stream(hb.stream):
+                fn()
+                hb.synchronize()
+                t2 = time.perf_counter()
+                for _ in range(reps):
+                    fn()
+                hb.synchronize()
+            us = (time.perf_counter() - t2) / reps / len(w.layers) * 1e6
+            graph_sweep = dict(graph_sweep or {}, **{f"{label}_us_per_launch": round(us, 2)})
+        graph_sweep["launches_per_sweep"] = len(w.layers)
+
     fused = None
     if w.N > 1:
         one_step_fused()
@@ -216,6 +239,7 @@ def main() -> int:
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},
         "fused_edges": fused,
+        "fold_sweep": graph_sweep,
         "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
                         "whole_model_bytes": w.P * w.grad_bytes},

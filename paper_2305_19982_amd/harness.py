@@ -179,5 +179,17 @@ class SimulatedBackward:
             self.micro_batch(lambda li, i=i: produce(i, li), N, beta1, beta2)
         self.apply(lr, eps, beta1, beta2)
 
+    # ---- HIP graph of a launch-bound sequence ----
+    def capture(self, enqueue: Callable[[], None]) -> "torch.cuda.CUDAGraph":
+        """Record everything `enqueue` launches on self.stream into a HIP graph and return it; replay with
+        graph.replay().  libadama's entry points neither allocate nor synchronise and carry their tensor
+        tables inside the kernel arguments, so they can be captured as they are.  The step counter is host
+        state: capture sequences whose scalars do not depend on t (decay and folds), or re-capture per step."""
+        graph = torch.cuda.CUDAGraph()
+        self.stream.synchronize()
+        with torch.cuda.graph(graph, stream=self.stream):
+            enqueue()
+        return graph
+
     def synchronize(self) -> None:
         self.stream.synchronize()

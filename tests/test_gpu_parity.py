@@ -378,3 +378,44 @@ def test_data_parallel_state_sync_arithmetic(torch_cuda, M, N):
             check_close(name, "v", v_sync.cpu().numpy(), rv)
             check_close(name, "theta", th, rt, prev_gpu, prev_ref)
         prev_gpu, prev_ref = th.copy(), ddp_theta.copy()
+
+
+# ---------------------------------------------------------------------------
+# HIP graph of a launch-bound sweep (many small tensors): replays equal eager launches bit for bit
+# ---------------------------------------------------------------------------
+def test_graph_replay_of_ragged_sweep_equals_eager(torch_cuda):
+    torch = torch_cuda
+    from paper_2305_19982_amd.harness import SimulatedBackward
+
+    w = configs.reduced("c4")
+    runs = {}
+    for mode in ("eager", "graph"):
+        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model")
+        for t in w.tensors:
+            synth.fill_device(hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, hb.stream_handle)
+
+        def sweep(hb=hb):
+            for li in w.backward_layers():
+                hb.fold_layer(li, w.N, w.beta1, w.beta2)
+
+        graph = hb.capture(sweep) if mode == "graph" else None
+        if graph is not None:           # capture does not execute: state is still untouched
+            hb.synchronize()
+            assert float(hb.m.abs().sum()) == 0.0
+        for step in range(1, 3):
+            hb.begin_step(w.beta1, w.beta2)
+            for i in range(w.N):
+                for t in w.tensors:     # new gradients before every replay, by eager launches between replays
+                    synth.fill_device(hb.grad_ptr(t.index), w.grad_spec(step, i, t.index), w.gdtype, t.n, hb.stream_handle)
+                if graph is not None:
+                    with torch.cuda.stream(hb.stream):
+                        graph.replay()
+                else:
+                    sweep()
+                hb.synchronize()        # host synchronisation between replays
+            hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+        hb.synchronize()
+        runs[mode] = (hb.theta.clone(), hb.m.clone(), hb.v.clone())
+    for a, b, name in zip(runs["eager"], runs["graph"], ("theta", "m", "v")):
+        assert torch.equal(a, b), f"{name}: graph replay differs from eager launches"
+    assert float(runs["graph"][2].sum()) > 0.0
