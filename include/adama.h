@@ -165,7 +165,7 @@ int adama_max_tensors_per_launch(void);
 /* Host-only: the launch policy compiled into the library, for benchmark labels.  A launch whose
  * tensors total at least *big_launch_elems elements uses chunks of 1024 * *u_big elements, shorter
  * launches use 1024 * *u_small; *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal
- * state loads, 4 = non-temporal stores, 8 = buffer-descriptor addressing.  Any pointer may be NULL. */
+ * state loads, 4 = non-temporal stores.  Any pointer may be NULL. */
 void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits);
 
 /*

@@ -145,6 +145,12 @@ __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint3
     const ADAMA_GLOBAL typename G::Vec *Gp = global_ptr<typename G::Vec>(d.g, e0 * sizeof(typename G::Elem));
     typename G::Vec g[U];
     f32x4 x[NS][U];
+    // All loads first, then, group by group, arithmetic and stores: a group's stores are issued as soon
+    // as its own loads have landed, while later groups' loads are still in flight.  The instruction
+    // scheduler is left free here on purpose.  Measured on 18 GB of state: holding every store back
+    // until all arithmetic is done costs 4 %, array-major order (all of g, all of m, all of v; stores
+    // likewise) costs 4 %, and pinning any fixed load order with scheduling barriers costs 1 %.
+    // (On small footprints array-major wins by 2 % instead; the order that holds up at scale is kept.)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const uint32_t i = u * kBlock + tid;
