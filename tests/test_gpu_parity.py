@@ -419,3 +419,132 @@ def test_graph_replay_of_ragged_sweep_equals_eager(torch_cuda):
     for a, b, name in zip(runs["eager"], runs["graph"], ("theta", "m", "v")):
         assert torch.equal(a, b), f"{name}: graph replay differs from eager launches"
     assert float(runs["graph"][2].sum()) > 0.0
+
+
+# ---------------------------------------------------------------------------
+# degenerate hyper-parameters and special values
+# ---------------------------------------------------------------------------
+def _one_step_against_oracle(torch, n, N, b1, b2, lr, eps, t, gdt="f32", grad_values=None, m0=None, v0=None):
+    from paper_2305_19982_amd import binding
+
+    key = synth.stream_key(77, n, N, t)
+    th0 = synth.fill_host(synth.Spec(key=key, sigma=0.02), "f32", n)
+    m0 = np.zeros(n, dtype=np.float32) if m0 is None else m0.astype(np.float32)
+    v0 = np.zeros(n, dtype=np.float32) if v0 is None else v0.astype(np.float32)
+    theta, m, v = (torch.from_numpy(x.copy()).cuda() for x in (th0, m0, v0))
+    ref = oracle.OracleState([th0])
+    ref.m[0][:] = m0
+    ref.v[0][:] = v0
+    ref.t = t - 1
+    binding.adama_begin_step(m, v, n, b1, b2)
+    ref.begin_step(b1, b2)
+    for i in range(N):
+        if grad_values is None:
+            g_host = synth.fill_host(synth.Spec(key=key + 1 + i, sigma=1e-2), gdt, n)
+        else:
+            g_host = grad_values[i]
+        g = torch.from_numpy(g_host.view(np.int16) if g_host.dtype == np.uint16 else g_host).cuda()
+        binding.adama_fold(m, v, g, gdt, n, N, b1, b2)
+        ref.fold(0, g_host, N, b1, b2, gdtype=None if gdt == "f32" else gdt)
+    binding.adama_apply(theta, m, v, n, lr, eps, b1, b2, t)
+    ref.apply(lr, eps, b1, b2)
+    torch.cuda.synchronize()
+    return (theta.cpu().numpy(), m.cpu().numpy(), v.cpu().numpy()), ref, th0
+
+
+@pytest.mark.parametrize("b1,b2,lr,eps,t", [(0.0, 0.999, 1e-3, 1e-8, 1), (0.9, 0.0, 1e-3, 1e-8, 1), (0.0, 0.0, 1e-2, 1e-6, 3),
+                                            (0.9, 0.999, 0.0, 1e-8, 2), (0.9, 0.999, 1e-3, 0.0, 5), (0.9, 0.999, 1e-3, 1e-8, 1000),
+                                            (0.99, 0.9999, 3e-4, 1e-12, 100000), (0.5, 0.5, -1e-3, 1e-3, 7)])
+def test_degenerate_hyper_parameters(torch_cuda, b1, b2, lr, eps, t):
+    n, N = 40961, 3
+    rng = np.random.default_rng(t)
+    m0 = rng.standard_normal(n) * 1e-3
+    v0 = np.abs(rng.standard_normal(n)) * 1e-5 + 1e-12          # v > 0 so that eps = 0 is well defined
+    (th, m, v), ref, th0 = _one_step_against_oracle(torch_cuda, n, N, b1, b2, lr, eps, t, m0=m0, v0=v0)
+    name = f"b1={b1} b2={b2} lr={lr} eps={eps} t={t}"
+    check_close(name, "m", m, ref.m[0])
+    check_close(name, "v", v, ref.v[0])
+    check_close(name, "theta", th, ref.theta[0], th0, th0.astype(np.float64))
+    if lr == 0.0:
+        assert np.array_equal(th, th0), "lr = 0 must leave theta untouched, bit for bit"
+
+
+def test_non_finite_gradients_propagate_by_ieee_rules(torch_cuda):
+    """No skip logic: an inf or nan gradient poisons exactly its own element, as in the oracle."""
+    n, N = 5000, 2
+    g0 = synth.fill_host(synth.Spec(key=5, sigma=1e-2), "f32", n)
+    g1 = synth.fill_host(synth.Spec(key=6, sigma=1e-2), "f32", n)
+    g0[7], g0[8], g1[9], g0[4097] = np.inf, -np.inf, np.nan, np.inf
+    (th, m, v), ref, th0 = _one_step_against_oracle(torch_cuda, n, N, B1, B2, LR, EPS, 1, grad_values=[g0, g1])
+    bad = np.zeros(n, dtype=bool)
+    bad[[7, 8, 9, 4097]] = True
+    with np.errstate(invalid="ignore"):
+        assert np.array_equal(np.isnan(th), np.isnan(ref.theta[0])) and np.array_equal(np.isnan(th), bad)
+        assert np.array_equal(np.isinf(m), np.isinf(ref.m[0])) and np.array_equal(np.isnan(m), np.isnan(ref.m[0]))
+        assert np.array_equal(np.isinf(v), np.isinf(ref.v[0])) and np.array_equal(np.isnan(v), np.isnan(ref.v[0]))
+    ok = ~bad
+    check_close("finite part", "m", m[ok], ref.m[0][ok])
+    check_close("finite part", "v", v[ok], ref.v[0][ok])
+    check_close("finite part", "theta", th[ok], ref.theta[0][ok])
+
+
+def test_float32_subnormal_moments_are_kept(torch_cuda):
+    """Denormal m and v are not flushed to zero by the decay or the fold."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n = 4099
+    tiny = np.float32(1e-41)
+    m = torch.full((n,), float(tiny), dtype=torch.float32, device="cuda:0")
+    v = torch.full((n,), float(tiny), dtype=torch.float32, device="cuda:0")
+    g = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    binding.adama_begin_step(m, v, n, 0.5, 0.5)
+    binding.adama_fold(m, v, g, "f32", n, 4, 0.9, 0.999)
+    torch.cuda.synchronize()
+    want = np.float32(tiny * np.float32(0.5))
+    assert want > 0
+    assert np.all(m.cpu().numpy() == want) and np.all(v.cpu().numpy() == want)
+
+
+def test_concurrent_host_threads_on_their_own_streams(torch_cuda):
+    """No shared mutable state in the library: two host threads drive independent tensors at once."""
+    import threading
+
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n, N, rounds = 300007, 4, 20
+    results, errors = {}, []
+
+    def worker(idx):
+        try:
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+                v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+                g = torch.zeros(n * 2, dtype=torch.uint8, device="cuda:0")
+            stream.synchronize()
+            for r in range(rounds):
+                synth.fill_device(g.data_ptr(), synth.Spec(key=1000 + r, sigma=1e-2), "bf16", n, stream.cuda_stream)
+                binding.adama_fold(m, v, g, "bf16", n, N, B1, B2, stream.cuda_stream)
+                try:
+                    binding.adama_fold(m, None, g, "bf16", n, N, B1, B2, stream.cuda_stream)   # errors stay thread-local
+                except binding.AdamaError as e:
+                    assert "v is NULL" in e.message
+            stream.synchronize()
+            results[idx] = (m.cpu().numpy(), v.cpu().numpy())
+        except Exception as e:   # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    assert np.array_equal(results[0][0], results[1][0]) and np.array_equal(results[0][1], results[1][1])
+    rm, rv = np.zeros(n), np.zeros(n)
+    for r in range(rounds):
+        oracle.fold(rm, rv, synth.fill_host(synth.Spec(key=1000 + r, sigma=1e-2), "bf16", n), N, B1, B2, gdtype="bf16")
+    check_close("threads", "m", results[0][0], rm)
+    check_close("threads", "v", results[0][1], rv)
