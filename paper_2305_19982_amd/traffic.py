@@ -37,7 +37,7 @@ def main() -> None:
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--kernel", default=r"multi_tensor_kernel<1, \d, 4, ", help="regex of the dominant kernel's name")
+    ap.add_argument("--kernel", default=r"multi_tensor_kernel<1, \d, 4, \d+, false>", help="regex of the dominant kernel's name")
     args = ap.parse_args()
     out = {"workload": args.workload, "unit": "bytes"}
     per_launch = {}
