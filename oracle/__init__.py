@@ -7,11 +7,17 @@ from .adama_oracle import (  # noqa: F401
     OracleState,
     alg1_step,
     apply,
+    apply_adamw,
     begin_step,
     bf16_to_f64,
     build,
     ddp_combine,
     f16_to_f64,
     fold,
+    fold_scaled,
     lib_path,
+    sgdm_apply,
+    sgdm_begin_step,
+    sgdm_fold,
+    widen,
 )

@@ -19,6 +19,14 @@
  * gradient closed form; v >= 0 and zero handling; sum-of-squares vs
  * square-of-sum relations; the multi-device equivalence of Sec. 3.3; element
  * independence; exhaustive bf16/fp16 widening against library conversions.
+ *
+ * The last part of the file carries the technique over to the variants the
+ * paper's conclusion points at (any momentum-based optimizer can fold and
+ * release gradients the same way): a loss-scale factor on the gradient,
+ * decoupled weight decay in the update (AdamW), and SGD with momentum.  The
+ * paper gives no formulas for these; each follows the optimizer's textbook
+ * definition and is pinned against a library implementation of that optimizer
+ * run on the mean gradient, plus closed forms.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -181,5 +189,99 @@ void adama_oracle_ddp_combine(double *m_out, double *v_out, const double *m_rank
         }
         m_out[k] = sum_m / (double)M;
         v_out[k] = sum_v / ((double)M * (double)M);
+    }
+}
+
+/* ================================================================== */
+/* Variants beyond the paper's algorithm boxes (Conclusion: the same    */
+/* fold-and-release works for any momentum-based optimizer).            */
+/* ================================================================== */
+
+/* Exact widening of a stored gradient tensor to double.                */
+/* gdt: 0 = binary32, 1 = bfloat16 bits, 2 = binary16 bits.             */
+int adama_oracle_widen(double *out, const void *grad, size_t n, int gdt)
+{
+    for (size_t k = 0; k < n; ++k) {
+        if (gdt == 0)
+            out[k] = (double)((const float *)grad)[k];
+        else if (gdt == 1)
+            out[k] = adama_oracle_bf16_to_f64(((const uint16_t *)grad)[k]);
+        else if (gdt == 2)
+            out[k] = adama_oracle_f16_to_f64(((const uint16_t *)grad)[k]);
+        else
+            return -1;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Fold of a gradient that was computed on a scaled loss (mixed         */
+/* precision with loss scaling): the true gradient is grad * grad_scale */
+/* with grad_scale = 1 / loss_scale, then Alg. 2's inner body as is.    */
+/*   g <- (1/N) * (grad_scale * grad)                                   */
+/*   m <- m + (1 - beta1) * g,   v <- v + (1 - beta2) * g^2             */
+/* ------------------------------------------------------------------ */
+void adama_oracle_fold_scaled(double *m, double *v, const double *grad, size_t n, int N,
+                              double beta1, double beta2, double grad_scale)
+{
+    for (size_t k = 0; k < n; ++k) {
+        double g = (grad_scale * grad[k]) / (double)N;
+        m[k] = m[k] + (1.0 - beta1) * g;
+        v[k] = v[k] + (1.0 - beta2) * (g * g);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Update with decoupled weight decay (AdamW): the decay acts on the    */
+/* parameter directly, scaled by the learning rate, and never enters    */
+/* m or v:                                                              */
+/*   theta <- theta - lr * lambda * theta - lr * m_hat/(sqrt(v_hat)+eps)*/
+/* Both terms use the parameter value from before the step.             */
+/* ------------------------------------------------------------------ */
+void adama_oracle_apply_adamw(double *theta, const double *m, const double *v, size_t n,
+                              double lr, double eps, double beta1, double beta2, long long t,
+                              double weight_decay)
+{
+    double bias1 = 1.0 - pow(beta1, (double)t);
+    double bias2 = 1.0 - pow(beta2, (double)t);
+    for (size_t k = 0; k < n; ++k) {
+        double m_hat = m[k] / bias1;
+        double v_hat = v[k] / bias2;
+        double decay = lr * weight_decay * theta[k];
+        theta[k] = theta[k] - decay - lr * m_hat / (sqrt(v_hat) + eps);
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* SGD with momentum, accumulated the AdamA way.  The textbook step on  */
+/* the mini-batch gradient g = (1/N) sum_i grad_i is                    */
+/*   b <- mu * b + g,   theta <- theta - lr * b.                        */
+/* b is linear in g, so it can be built one micro-batch and one layer   */
+/* at a time exactly as AdamA builds m:                                 */
+/*   once per mini-batch:        b <- mu * b                            */
+/*   per layer per micro-batch:  b <- b + (grad_scale * grad) / N       */
+/*   once per mini-batch:        theta <- theta - lr*lambda*theta - lr*b*/
+/* (lambda: decoupled weight decay, 0 for plain SGD).                   */
+/* ------------------------------------------------------------------ */
+void adama_oracle_sgdm_begin_step(double *b, size_t n, double mu)
+{
+    for (size_t k = 0; k < n; ++k)
+        b[k] = mu * b[k];
+}
+
+void adama_oracle_sgdm_fold(double *b, const double *grad, size_t n, int N, double grad_scale)
+{
+    for (size_t k = 0; k < n; ++k) {
+        double g = (grad_scale * grad[k]) / (double)N;
+        b[k] = b[k] + g;
+    }
+}
+
+void adama_oracle_sgdm_apply(double *theta, const double *b, size_t n, double lr,
+                             double weight_decay)
+{
+    for (size_t k = 0; k < n; ++k) {
+        double decay = lr * weight_decay * theta[k];
+        theta[k] = theta[k] - decay - lr * b[k];
     }
 }

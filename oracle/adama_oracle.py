@@ -65,6 +65,18 @@ def load(path: str | None = None) -> ctypes.CDLL:
     lib.adama_oracle_alg1_step.argtypes = [_dp, _dp, _dp, _dp, sz, i32, i32, dbl, dbl, dbl, dbl, i64]
     lib.adama_oracle_ddp_combine.restype = None
     lib.adama_oracle_ddp_combine.argtypes = [_dp, _dp, _dp, _dp, sz, i32]
+    lib.adama_oracle_widen.restype = i32
+    lib.adama_oracle_widen.argtypes = [_dp, vp, sz, i32]
+    lib.adama_oracle_fold_scaled.restype = None
+    lib.adama_oracle_fold_scaled.argtypes = [_dp, _dp, _dp, sz, i32, dbl, dbl, dbl]
+    lib.adama_oracle_apply_adamw.restype = None
+    lib.adama_oracle_apply_adamw.argtypes = [_dp, _dp, _dp, sz, dbl, dbl, dbl, dbl, i64, dbl]
+    lib.adama_oracle_sgdm_begin_step.restype = None
+    lib.adama_oracle_sgdm_begin_step.argtypes = [_dp, sz, dbl]
+    lib.adama_oracle_sgdm_fold.restype = None
+    lib.adama_oracle_sgdm_fold.argtypes = [_dp, _dp, sz, i32, dbl]
+    lib.adama_oracle_sgdm_apply.restype = None
+    lib.adama_oracle_sgdm_apply.argtypes = [_dp, _dp, sz, dbl, dbl]
     return lib
 
 
@@ -161,6 +173,65 @@ def ddp_combine(m_ranks, v_ranks, lib=None):
                                              _f64_ro(m_ranks, "m_ranks"),
                                              _f64_ro(v_ranks, "v_ranks"), n, M)
     return m_out, v_out
+
+
+def widen(grad: np.ndarray, gdtype: str | None = None, lib=None) -> np.ndarray:
+    """Exact float64 copy of a stored gradient: float32, float16, or uint16 bits ("bf16"/"f16")."""
+    grad = np.ascontiguousarray(grad).reshape(-1)
+    if grad.dtype == np.float64 and gdtype in (None, "f64"):
+        return grad.copy()
+    if grad.dtype == np.float32 and gdtype in (None, "f32"):
+        code = 0
+    elif grad.dtype == np.uint16 and gdtype == "bf16":
+        code = 1
+    elif (grad.dtype == np.uint16 and gdtype == "f16") or (grad.dtype == np.float16 and gdtype in (None, "f16")):
+        code = 2
+    else:
+        raise TypeError(f"unsupported gradient dtype {grad.dtype} / {gdtype}")
+    out = np.empty(grad.size, dtype=np.float64)
+    rc = (lib or _get()).adama_oracle_widen(_f64(out, "out"), ctypes.c_void_p(grad.ctypes.data), grad.size, code)
+    assert rc == 0
+    return out
+
+
+def fold_scaled(m, v, grad, N: int, beta1: float, beta2: float, grad_scale: float, gdtype: str | None = None,
+                lib=None) -> None:
+    """Fold of a gradient taken on a scaled loss: the gradient is grad * grad_scale (in place on m, v)."""
+    assert m.size == v.size == grad.size
+    if N < 1:
+        raise ValueError("N must be >= 1")
+    g64 = widen(grad, gdtype, lib=lib)
+    (lib or _get()).adama_oracle_fold_scaled(_f64(m, "m"), _f64(v, "v"), _f64_ro(g64, "grad"), m.size, int(N),
+                                             beta1, beta2, grad_scale)
+
+
+def apply_adamw(theta, m, v, lr, eps, beta1, beta2, t: int, weight_decay: float, lib=None) -> None:
+    """Update with decoupled weight decay (in place on theta), t >= 1."""
+    assert theta.size == m.size == v.size
+    if t < 1:
+        raise ValueError("t must be >= 1")
+    (lib or _get()).adama_oracle_apply_adamw(_f64(theta, "theta"), _f64_ro(m, "m"), _f64_ro(v, "v"), theta.size,
+                                             lr, eps, beta1, beta2, int(t), weight_decay)
+
+
+def sgdm_begin_step(b, mu: float, lib=None) -> None:
+    """Momentum SGD, once per mini-batch: b <- mu b (in place)."""
+    (lib or _get()).adama_oracle_sgdm_begin_step(_f64(b, "b"), b.size, mu)
+
+
+def sgdm_fold(b, grad, N: int, grad_scale: float = 1.0, gdtype: str | None = None, lib=None) -> None:
+    """Momentum SGD, per layer per micro-batch: b <- b + grad_scale * grad / N (in place)."""
+    assert b.size == grad.size
+    if N < 1:
+        raise ValueError("N must be >= 1")
+    g64 = widen(grad, gdtype, lib=lib)
+    (lib or _get()).adama_oracle_sgdm_fold(_f64(b, "b"), _f64_ro(g64, "grad"), b.size, int(N), grad_scale)
+
+
+def sgdm_apply(theta, b, lr: float, weight_decay: float = 0.0, lib=None) -> None:
+    """Momentum SGD, once per mini-batch: theta <- theta - lr*weight_decay*theta - lr*b (in place)."""
+    assert theta.size == b.size
+    (lib or _get()).adama_oracle_sgdm_apply(_f64(theta, "theta"), _f64_ro(b, "b"), theta.size, lr, weight_decay)
 
 
 class OracleState:

@@ -394,6 +394,175 @@ def pin_element_independence(lib, kinds=GRAD_KINDS):
             assert np.array_equal(np.concatenate(getattr(pieces, name)), w)
 
 
+# --------------------------------------------------------------------------
+# variants beyond the paper's algorithm boxes: loss-scale factor, AdamW, momentum SGD
+# --------------------------------------------------------------------------
+def pin_widen_tensor(lib):
+    """The tensor widening used by the variant folds: all 16-bit patterns and random float32,
+    against library conversions."""
+    import torch
+
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    ref16 = bits.view(np.float16).astype(np.float64)
+    refbf = torch.from_numpy(bits.view(np.int16).copy()).view(torch.bfloat16).to(torch.float64).numpy()
+    for kind, ref in (("f16", ref16), ("bf16", refbf)):
+        got = oracle.widen(bits.copy(), kind, lib=lib)
+        nan = np.isnan(ref)
+        assert np.array_equal(np.isnan(got), nan), f"{kind}: NaN patterns differ"
+        assert np.array_equal(got[~nan], ref[~nan]) and np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan])), kind
+    f = np.random.default_rng(3).standard_normal(4099).astype(np.float32)
+    assert np.array_equal(oracle.widen(f, lib=lib), f.astype(np.float64))
+
+
+def pin_fold_scaled_exact(lib, kinds=GRAD_KINDS):
+    """One scaled fold from known state against exact rational arithmetic, and the scaling
+    invariant: a gradient stored 2^k times too large with grad_scale = 2^-k folds to the very
+    bits of the plain fold of the true gradient."""
+    from fractions import Fraction
+
+    N, b1, b2, s = 3, 0.875, 0.96875, 1.0 / 1024.0
+    g = np.array([0.5, -1.25, 3.0, 0.0, -0.0078125, 24.0])
+    m0 = np.array([0.25, -0.5, 0.0, 1.0, 2.0, -3.0])
+    v0 = np.array([0.125, 0.5, 0.0, 0.25, 4.0, 9.0])
+    for kind in kinds:
+        arr, gdt, exact = encode_grad(g * 1024.0, kind)
+        assert np.array_equal(exact, g * 1024.0)
+        m, v = m0.copy(), v0.copy()
+        oracle.fold_scaled(m, v, arr, N, b1, b2, s, gdtype=gdt, lib=lib)
+        for k in range(g.size):
+            gk = Fraction(float(g[k])) / N
+            em = Fraction(float(m0[k])) + (1 - Fraction(b1)) * gk
+            ev = Fraction(float(v0[k])) + (1 - Fraction(b2)) * gk * gk
+            assert abs(Fraction(float(m[k])) - em) <= abs(em) * Fraction(1, 10 ** 15), f"scaled fold m[{k}] {kind}"
+            assert abs(Fraction(float(v[k])) - ev) <= abs(ev) * Fraction(1, 10 ** 15), f"scaled fold v[{k}] {kind}"
+    rng = np.random.default_rng(23)
+    g = _rand_grads(rng, 777)
+    m1, v1 = rng.standard_normal(777) * 1e-3, rng.random(777) * 1e-6
+    m2, v2 = m1.copy(), v1.copy()
+    oracle.fold(m1, v1, g, 4, B1, B2, lib=lib)
+    oracle.fold_scaled(m2, v2, g * 4096.0, 4, B1, B2, 1.0 / 4096.0, lib=lib)
+    assert np.array_equal(m1, m2) and np.array_equal(v1, v2), "power-of-two loss scale must cancel exactly"
+
+
+def pin_adamw_library(lib):
+    """N=1 with decoupled weight decay against torch.optim.AdamW in fp64 on the CPU; the moments
+    must not see the decay (they equal plain Adam's)."""
+    import torch
+
+    rng = np.random.default_rng(29)
+    n, T, wd, lr = 1283, 7, 0.1, 2e-3
+    theta0 = rng.standard_normal(n) * 0.5
+    p = torch.nn.Parameter(torch.from_numpy(theta0.copy()))
+    opt = torch.optim.AdamW([p], lr=lr, betas=(B1, B2), eps=EPS, weight_decay=wd, amsgrad=False, foreach=False,
+                            fused=False)
+    q = torch.nn.Parameter(torch.from_numpy(theta0.copy()))
+    plain = torch.optim.Adam([q], lr=lr, betas=(B1, B2), eps=EPS, foreach=False, fused=False)
+    theta, m, v = theta0.copy(), np.zeros(n), np.zeros(n)
+    for t in range(1, T + 1):
+        g = _rand_grads(rng, n, sigma=3e-3)
+        p.grad = torch.from_numpy(g.copy())
+        q.grad = torch.from_numpy(g.copy())
+        opt.step()
+        plain.step()
+        oracle.begin_step(m, v, B1, B2, lib=lib)
+        oracle.fold(m, v, g, 1, B1, B2, lib=lib)
+        oracle.apply_adamw(theta, m, v, lr, EPS, B1, B2, t, wd, lib=lib)
+        rel_close(theta, p.detach().numpy(), 1e-12, f"library AdamW theta t={t}")
+        rel_close(v, plain.state[q]["exp_avg_sq"].numpy(), 1e-12, f"AdamW v == Adam v t={t}")
+    assert np.max(np.abs(theta - q.detach().numpy())) > 1e-4, "weight decay had no effect"
+
+
+def pin_adamw_closed_forms(lib):
+    """Zero moments: theta_T = theta_0 (1 - lr*lambda)^T exactly as a product.  lambda = 0: the
+    very bits of the plain update.  One step from given state against exact rationals up to the
+    square root."""
+    rng = np.random.default_rng(31)
+    n, lr, wd = 257, 0.05, 0.3
+    theta0 = rng.standard_normal(n)
+    theta = theta0.copy()
+    z = np.zeros(n)
+    for t in range(1, 6):
+        oracle.apply_adamw(theta, z, z, lr, EPS, B1, B2, t, wd, lib=lib)
+        rel_close(theta, theta0 * (1.0 - lr * wd) ** t, 1e-14, f"pure decay t={t}")
+    m, v = rng.standard_normal(n) * 1e-2, rng.random(n) * 1e-4
+    a, b = theta0.copy(), theta0.copy()
+    oracle.apply(a, m, v, LR, EPS, B1, B2, 3, lib=lib)
+    oracle.apply_adamw(b, m, v, LR, EPS, B1, B2, 3, 0.0, lib=lib)
+    assert np.array_equal(a, b), "lambda = 0 must reproduce the plain update"
+    # decay and Adam step are additive: theta_w - theta_plain = -lr*lambda*theta_0
+    c = theta0.copy()
+    oracle.apply_adamw(c, m, v, LR, EPS, B1, B2, 3, wd, lib=lib)
+    err = np.abs((c - a) + LR * wd * theta0)
+    assert np.all(err <= 4e-16 * np.abs(theta0) + 1e-300), "decay term is not -lr*lambda*theta_0"
+
+
+def pin_sgdm_library(lib, kinds=GRAD_KINDS):
+    """Momentum SGD accumulated per micro-batch against torch.optim.SGD(momentum) in fp64 on the
+    mean gradient: the buffer and the parameters agree to rounding."""
+    import torch
+
+    rng = np.random.default_rng(37)
+    n, T, N, mu, lr = 1031, 5, 4, 0.9, 0.05
+    for kind in kinds:
+        theta0 = rng.standard_normal(n) * 0.1
+        p = torch.nn.Parameter(torch.from_numpy(theta0.copy()))
+        opt = torch.optim.SGD([p], lr=lr, momentum=mu, dampening=0.0, weight_decay=0.0, nesterov=False, foreach=False)
+        theta, b = theta0.copy(), np.zeros(n)
+        for t in range(1, T + 1):
+            oracle.sgdm_begin_step(b, mu, lib=lib)
+            mean = np.zeros(n)
+            for i in range(N):
+                arr, gdt, exact = encode_grad(_rand_grads(rng, n), kind)
+                oracle.sgdm_fold(b, arr, N, 1.0, gdtype=gdt, lib=lib)
+                mean += exact / N
+            oracle.sgdm_apply(theta, b, lr, 0.0, lib=lib)
+            p.grad = torch.from_numpy(mean.copy())
+            opt.step()
+            ref_b = opt.state[p]["momentum_buffer"].numpy()
+            scale = np.sqrt(np.mean(ref_b ** 2))
+            assert np.max(np.abs(b - ref_b)) <= 1e-13 * scale, f"SGD momentum buffer t={t} {kind}"
+            assert np.max(np.abs(theta - p.detach().numpy())) <= 1e-13 * np.max(np.abs(theta0)), f"SGD theta t={t} {kind}"
+
+
+def pin_sgdm_closed_forms(lib):
+    """Constant gradient c: b_T = c (1 - mu^T)/(1 - mu), theta_T = theta_0 - lr * sum_t b_t.
+    Zero gradient with decay: theta_T = theta_0 (1 - lr*lambda)^T.  Loss scale: exact rationals."""
+    from fractions import Fraction
+
+    n, N, mu, lr, T = 65, 4, 0.75, 0.125, 6
+    c = np.linspace(-2.0, 2.0, n)
+    theta0 = np.linspace(1.0, 3.0, n)
+    theta, b = theta0.copy(), np.zeros(n)
+    acc = np.zeros(n)
+    for t in range(1, T + 1):
+        oracle.sgdm_begin_step(b, mu, lib=lib)
+        for i in range(N):
+            oracle.sgdm_fold(b, c, N, 1.0, lib=lib)
+        oracle.sgdm_apply(theta, b, lr, 0.0, lib=lib)
+        bt = c * (1.0 - mu ** t) / (1.0 - mu)
+        acc += bt
+        assert np.max(np.abs(b - bt)) <= 1e-14 * np.max(np.abs(bt)), f"constant gradient buffer t={t}"
+        assert np.max(np.abs(theta - (theta0 - lr * acc))) <= 1e-14 * np.max(np.abs(theta0)), f"constant gradient theta t={t}"
+    theta = theta0.copy()
+    z = np.zeros(n)
+    for t in range(1, 5):
+        oracle.sgdm_apply(theta, z, lr, 0.5, lib=lib)
+        rel_close(theta, theta0 * (1.0 - lr * 0.5) ** t, 1e-14, f"SGD pure decay t={t}")
+    g = np.array([3.0, -0.375, 640.0])
+    b0 = np.array([1.0, -2.0, 0.5])
+    b = b0.copy()
+    oracle.sgdm_fold(b, g, 3, 1.0 / 64.0, lib=lib)
+    for k in range(3):
+        eb = Fraction(float(b0[k])) + Fraction(float(g[k])) / 64 / 3
+        assert abs(Fraction(float(b[k])) - eb) <= abs(eb) * Fraction(1, 10 ** 15), f"scaled SGD fold [{k}]"
+    th = np.array([2.0, -4.0, 8.0])
+    th0 = th.copy()
+    oracle.sgdm_apply(th, b0, 0.25, 0.5, lib=lib)
+    for k in range(3):
+        e = Fraction(float(th0[k])) * (1 - Fraction(1, 8)) - Fraction(1, 4) * Fraction(float(b0[k]))
+        assert Fraction(float(th[k])) == e, f"SGD apply [{k}]"
+
+
 ALL_PINS = (
     pin_widening,
     pin_tiny_exact,
@@ -405,4 +574,10 @@ ALL_PINS = (
     pin_adam_vs_adama_second_moment,
     pin_ddp_equivalence,
     pin_element_independence,
+    pin_widen_tensor,
+    pin_fold_scaled_exact,
+    pin_adamw_library,
+    pin_adamw_closed_forms,
+    pin_sgdm_library,
+    pin_sgdm_closed_forms,
 )

@@ -52,6 +52,29 @@ MUTANTS = [
     ("f16_hidden_bit", "(double)(1024 + frac)", "(double)(frac)", 0),
     ("f16_sign_dropped", "return sign ? -mag : mag;", "return mag;", 0),
     ("bf16_shift", "(uint32_t)bits << 16", "(uint32_t)bits << 15", 0),
+    # variants: loss-scale factor, AdamW, momentum SGD
+    ("widen_formats_swapped", "else if (gdt == 1)", "else if (gdt == 2 || gdt == 1)", 0),
+    ("widen_f32_truncated", "out[k] = (double)((const float *)grad)[k];", "out[k] = (double)(int)((const float *)grad)[k];", 0),
+    ("scaled_fold_scale_dropped", "double g = (grad_scale * grad[k]) / (double)N;", "double g = grad[k] / (double)N;", 0),
+    ("scaled_fold_scale_inverted", "double g = (grad_scale * grad[k]) / (double)N;", "double g = (grad[k] / grad_scale) / (double)N;", 0),
+    ("scaled_fold_no_div_N", "double g = (grad_scale * grad[k]) / (double)N;", "double g = (grad_scale * grad[k]);", 0),
+    ("adamw_decay_sign", "theta[k] - decay - lr * m_hat", "theta[k] + decay - lr * m_hat", 0),
+    ("adamw_decay_without_lr", "double decay = lr * weight_decay * theta[k];", "double decay = weight_decay * theta[k];", 0),
+    ("adamw_decay_dropped", "theta[k] - decay - lr * m_hat", "theta[k] - lr * m_hat", 0),
+    ("adamw_eps_inside_sqrt", "/ (sqrt(v_hat) + eps);", "/ sqrt(v_hat + eps);", 1),
+    ("adamw_no_bias1", "double m_hat = m[k] / bias1;", "double m_hat = m[k];", 1),
+    ("adamw_no_bias2", "double v_hat = v[k] / bias2;", "double v_hat = v[k];", 1),
+    ("adamw_step_sign", "- decay - lr * m_hat", "- decay + lr * m_hat", 0),
+    ("sgdm_decay_missing", "b[k] = mu * b[k];", "b[k] = b[k];", 0),
+    ("sgdm_fold_overwrites", "b[k] = b[k] + g;", "b[k] = g;", 0),
+    ("sgdm_fold_sign", "b[k] = b[k] + g;", "b[k] = b[k] - g;", 0),
+    ("sgdm_fold_no_div_N", "double g = (grad_scale * grad[k]) / (double)N;", "double g = (grad_scale * grad[k]);", 1),
+    ("sgdm_fold_scale_dropped", "double g = (grad_scale * grad[k]) / (double)N;", "double g = grad[k] / (double)N;", 1),
+    ("sgdm_fold_dampened", "b[k] = b[k] + g;", "b[k] = b[k] + (1.0 - 0.9) * g;", 0),
+    ("sgdm_apply_sign", "theta[k] - decay - lr * b[k];", "theta[k] - decay + lr * b[k];", 0),
+    ("sgdm_apply_no_lr", "theta[k] - decay - lr * b[k];", "theta[k] - decay - b[k];", 0),
+    ("sgdm_apply_decay_without_lr", "double decay = lr * weight_decay * theta[k];", "double decay = weight_decay * theta[k];", 1),
+    ("sgdm_apply_decay_sign", "theta[k] - decay - lr * b[k];", "theta[k] + decay - lr * b[k];", 0),
 ]
 
 
