@@ -154,6 +154,81 @@ adama_status adama_rescale_apply(float *theta, float *m, float *v, size_t n, dou
 adama_status adama_rescale_apply_multi(const adama_state *list, int count, double m_scale, double v_scale, double lr,
                                        double eps, double beta1, double beta2, long long t, hipStream_t stream);
 
+/* ------------------------------------------------------------------------------------------------
+ * Variants.  The paper's Conclusion notes that the same scheme -- fold each gradient into the
+ * optimizer state as it is produced, then release it -- serves any momentum-based optimizer.  The
+ * calls below carry it to Adam with decoupled weight decay (AdamW), to gradients taken on a scaled
+ * loss (mixed-precision loss scaling), and to SGD with momentum.  The paper gives no formulas for
+ * these; each follows the optimizer's usual definition, stated at the call.
+ * ------------------------------------------------------------------------------------------------ */
+
+/* Options of the *_opt calls.  A NULL pointer means {0.0, 1.0}, which makes every *_opt call
+ * bit-identical to the call without the suffix. */
+typedef struct {
+    double weight_decay;  /* lambda >= 0, finite.  Decoupled decay: an update also subtracts
+                             lr * lambda * theta[k] (theta from before the step); the moments never see it. */
+    double grad_scale;    /* s > 0, finite.  Every gradient element is multiplied by s before use
+                             (s = 1 / loss_scale when the loss was scaled up for float16 gradients). */
+} adama_options;
+
+/* adama_fold_multi / adama_fold_first_multi with g = opt->grad_scale * grad[k] / N.  The factor is
+ * folded into the two host-side constants, so traffic and kernels are those of the plain calls. */
+adama_status adama_fold_opt_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                                  double beta2, const adama_options *opt, hipStream_t stream);
+adama_status adama_fold_first_opt_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                                        double beta2, const adama_options *opt, hipStream_t stream);
+
+/* adama_apply_multi with decoupled weight decay:
+ *     theta[k] <- theta[k] - (lr * lambda * theta[k] + lr * m_hat / (sqrt(v_hat) + eps))
+ * (opt->grad_scale is not used: the moments already hold unscaled gradients). */
+adama_status adama_apply_opt_multi(const adama_state *list, int count, double lr, double eps, double beta1,
+                                   double beta2, long long t, const adama_options *opt, hipStream_t stream);
+
+/* adama_fold_last_apply_multi with both options: bit-identical to adama_fold_opt_multi followed by
+ * adama_apply_opt_multi. */
+adama_status adama_fold_last_apply_opt_multi(const adama_update_tensor *list, int count, adama_dtype gdt, int N,
+                                             double lr, double eps, double beta1, double beta2, long long t,
+                                             const adama_options *opt, hipStream_t stream);
+
+/* adama_rescale_apply_multi with decoupled weight decay. */
+adama_status adama_rescale_apply_opt_multi(const adama_state *list, int count, double m_scale, double v_scale,
+                                           double lr, double eps, double beta1, double beta2, long long t,
+                                           const adama_options *opt, hipStream_t stream);
+
+/* One tensor of an SGD-with-momentum list.  Fields a call does not use may be NULL. */
+typedef struct {
+    float *theta;      /* device, n floats; read and written by the two apply calls */
+    float *b;          /* device, n floats; the momentum buffer */
+    const void *grad;  /* device, n elements of the list's gradient dtype; read by the three fold calls */
+    size_t n;
+} adama_sgdm_tensor;
+
+/* SGD with momentum mu on the mini-batch gradient g = (1/N) sum_i grad_i is
+ *     b <- mu * b + g,   theta <- theta - lr * b            (no dampening, no Nesterov term).
+ * b is linear in g, so it is built one layer of one micro-batch at a time, as AdamA builds m, and the
+ * result equals the textbook step up to rounding (nothing is approximated, unlike AdamA's v):
+ *
+ *     adama_sgdm_begin_step_multi        once per mini-batch:         b[k] <- mu * b[k]
+ *     adama_sgdm_fold_multi              per layer per micro-batch:   b[k] <- b[k] + s * grad[k] / N
+ *     adama_sgdm_apply_multi             once per mini-batch:         theta[k] <- theta[k] - (lr*lambda*theta[k] + lr*b[k])
+ *
+ * and the fused edge forms, bit-identical to the separate calls:
+ *
+ *     adama_sgdm_fold_first_multi        micro-batch 0:    b[k] <- mu * b[k] + s * grad[k] / N
+ *     adama_sgdm_fold_last_apply_multi   micro-batch N-1:  the fold, then the update with the new b
+ *
+ * mu finite and >= 0; N >= 1; lr finite; s and lambda from `opt` (NULL: s = 1, lambda = 0).
+ * Traffic per element: 8 B decay, 8 B + gradient fold, 12 B apply, 16 B + gradient fold_last_apply. */
+adama_status adama_sgdm_begin_step_multi(const adama_sgdm_tensor *list, int count, double momentum, hipStream_t stream);
+adama_status adama_sgdm_fold_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                   const adama_options *opt, hipStream_t stream);
+adama_status adama_sgdm_fold_first_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                         double momentum, const adama_options *opt, hipStream_t stream);
+adama_status adama_sgdm_apply_multi(const adama_sgdm_tensor *list, int count, double lr, const adama_options *opt,
+                                    hipStream_t stream);
+adama_status adama_sgdm_fold_last_apply_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                              double lr, const adama_options *opt, hipStream_t stream);
+
 /* Message of the last failing call on this thread ("" if none).  Valid until the next call
  * on the same thread. */
 const char *adama_last_error(void);
@@ -174,8 +249,8 @@ void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems
  * for each element e of tensor k an access covers (touched[k] is a host array of list[k].n bytes,
  * zero-filled by the caller).  op: 0 decay (m, v), 1 fold (m, v, grad), 2 apply (theta, m, v),
  * 3 fold_first (m, v, grad), 4 fold_last_apply (theta, m, v, grad), 5 rescale_apply (theta, m, v);
- * fields an op does not use are
- * ignored.  *vector_accesses and *scalar_accesses count 16-byte and single-element accesses.
+ * 6..10 the SGD-with-momentum decay, fold, apply, fold_first, fold_last_apply, whose buffer b is
+ * passed in the m field.  Fields an op does not use are ignored.  *vector_accesses and *scalar_accesses count 16-byte and single-element accesses.
  * Returns ADAMA_ERR_INVALID_ARG if an access would leave a tensor or a vector access would be
  * misaligned.  Used by the CPU test-suite.
  */

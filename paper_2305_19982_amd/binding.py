@@ -44,6 +44,14 @@ class adama_state(ctypes.Structure):
     _fields_ = [("theta", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p), ("n", ctypes.c_size_t)]
 
 
+class adama_options(ctypes.Structure):
+    _fields_ = [("weight_decay", ctypes.c_double), ("grad_scale", ctypes.c_double)]
+
+
+class adama_sgdm_tensor(ctypes.Structure):
+    _fields_ = [("theta", ctypes.c_void_p), ("b", ctypes.c_void_p), ("grad", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
 _lib = None
 
 
@@ -76,6 +84,25 @@ def load() -> ctypes.CDLL:
     lib.adama_debug_walk.argtypes = [ctypes.POINTER(adama_update_tensor), i32, i32, i32, ctypes.POINTER(vp),
                                      ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(ctypes.c_ulonglong),
                                      ctypes.POINTER(i32)]
+    optp = ctypes.POINTER(adama_options)
+    sgdp = ctypes.POINTER(adama_sgdm_tensor)
+    lib.adama_fold_opt_multi.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, dbl, dbl, optp, vp]
+    lib.adama_fold_first_opt_multi.argtypes = [ctypes.POINTER(adama_tensor), i32, i32, i32, dbl, dbl, optp, vp]
+    lib.adama_fold_last_apply_opt_multi.argtypes = [ctypes.POINTER(adama_update_tensor), i32, i32, i32, dbl, dbl, dbl,
+                                                    dbl, i64, optp, vp]
+    lib.adama_apply_opt_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, i64, optp, vp]
+    lib.adama_rescale_apply_opt_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, dbl, dbl, dbl, dbl, i64,
+                                                  optp, vp]
+    lib.adama_sgdm_begin_step_multi.argtypes = [sgdp, i32, dbl, vp]
+    lib.adama_sgdm_fold_multi.argtypes = [sgdp, i32, i32, i32, optp, vp]
+    lib.adama_sgdm_fold_first_multi.argtypes = [sgdp, i32, i32, i32, dbl, optp, vp]
+    lib.adama_sgdm_apply_multi.argtypes = [sgdp, i32, dbl, optp, vp]
+    lib.adama_sgdm_fold_last_apply_multi.argtypes = [sgdp, i32, i32, i32, dbl, optp, vp]
+    for name in ("adama_fold_opt_multi", "adama_fold_first_opt_multi", "adama_fold_last_apply_opt_multi",
+                 "adama_apply_opt_multi", "adama_rescale_apply_opt_multi", "adama_sgdm_begin_step_multi",
+                 "adama_sgdm_fold_multi", "adama_sgdm_fold_first_multi", "adama_sgdm_apply_multi",
+                 "adama_sgdm_fold_last_apply_multi"):
+        getattr(lib, name).restype = i32
     for name in ("adama_begin_step", "adama_begin_step_multi", "adama_fold", "adama_fold_multi", "adama_apply",
                  "adama_apply_multi", "adama_fold_first", "adama_fold_first_multi", "adama_fold_last_apply",
                  "adama_fold_last_apply_multi", "adama_rescale_apply", "adama_rescale_apply_multi",
@@ -213,6 +240,102 @@ def adama_rescale_apply_multi(lst, count: int | None, m_scale: float, v_scale: f
         lst = state_list(lst)
     _check(load().adama_rescale_apply_multi(lst, len(lst) if count is None else count, m_scale, v_scale, lr, eps,
                                             beta1, beta2, t, stream))
+
+
+def options(weight_decay: float = 0.0, grad_scale: float = 1.0) -> adama_options:
+    return adama_options(weight_decay, grad_scale)
+
+
+def _opt(opt):
+    """None (-> NULL), an adama_options, or a (weight_decay, grad_scale) pair."""
+    if opt is None:
+        return None
+    if isinstance(opt, adama_options):
+        return ctypes.byref(opt)
+    return ctypes.byref(adama_options(float(opt[0]), float(opt[1])))
+
+
+def sgdm_list(entries) -> ctypes.Array:
+    """Host array of adama_sgdm_tensor from (theta, b, grad, n) tuples; reusable across calls."""
+    arr = (adama_sgdm_tensor * len(entries))()
+    for i, (th, b, g, n) in enumerate(entries):
+        arr[i] = adama_sgdm_tensor(_ptr(th), _ptr(b), _ptr(g), int(n))
+    return arr
+
+
+def adama_fold_opt_multi(lst, count: int | None, gdt, N: int, beta1: float, beta2: float, opt=None,
+                         stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = tensor_list(lst)
+    _check(load().adama_fold_opt_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N, beta1,
+                                       beta2, _opt(opt), stream))
+
+
+def adama_fold_first_opt_multi(lst, count: int | None, gdt, N: int, beta1: float, beta2: float, opt=None,
+                               stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = tensor_list(lst)
+    _check(load().adama_fold_first_opt_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N,
+                                             beta1, beta2, _opt(opt), stream))
+
+
+def adama_fold_last_apply_opt_multi(lst, count: int | None, gdt, N: int, lr: float, eps: float, beta1: float,
+                                    beta2: float, t: int, opt=None, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = update_list(lst)
+    _check(load().adama_fold_last_apply_opt_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N,
+                                                  lr, eps, beta1, beta2, t, _opt(opt), stream))
+
+
+def adama_apply_opt_multi(lst, count: int | None, lr: float, eps: float, beta1: float, beta2: float, t: int,
+                          opt=None, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = state_list(lst)
+    _check(load().adama_apply_opt_multi(lst, len(lst) if count is None else count, lr, eps, beta1, beta2, t,
+                                        _opt(opt), stream))
+
+
+def adama_rescale_apply_opt_multi(lst, count: int | None, m_scale: float, v_scale: float, lr: float, eps: float,
+                                  beta1: float, beta2: float, t: int, opt=None, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = state_list(lst)
+    _check(load().adama_rescale_apply_opt_multi(lst, len(lst) if count is None else count, m_scale, v_scale, lr, eps,
+                                                beta1, beta2, t, _opt(opt), stream))
+
+
+def adama_sgdm_begin_step_multi(lst, count: int | None, momentum: float, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = sgdm_list(lst)
+    _check(load().adama_sgdm_begin_step_multi(lst, len(lst) if count is None else count, momentum, stream))
+
+
+def adama_sgdm_fold_multi(lst, count: int | None, gdt, N: int, opt=None, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = sgdm_list(lst)
+    _check(load().adama_sgdm_fold_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N, _opt(opt),
+                                        stream))
+
+
+def adama_sgdm_fold_first_multi(lst, count: int | None, gdt, N: int, momentum: float, opt=None,
+                                stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = sgdm_list(lst)
+    _check(load().adama_sgdm_fold_first_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N,
+                                              momentum, _opt(opt), stream))
+
+
+def adama_sgdm_apply_multi(lst, count: int | None, lr: float, opt=None, stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = sgdm_list(lst)
+    _check(load().adama_sgdm_apply_multi(lst, len(lst) if count is None else count, lr, _opt(opt), stream))
+
+
+def adama_sgdm_fold_last_apply_multi(lst, count: int | None, gdt, N: int, lr: float, opt=None,
+                                     stream: int = 0) -> None:
+    if not isinstance(lst, ctypes.Array):
+        lst = sgdm_list(lst)
+    _check(load().adama_sgdm_fold_last_apply_multi(lst, len(lst) if count is None else count, DTYPES.get(gdt, gdt), N,
+                                                   lr, _opt(opt), stream))
 
 
 def adama_debug_walk(entries, op: int, gdt):

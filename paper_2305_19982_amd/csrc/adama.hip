@@ -122,8 +122,14 @@ adama_status launch_all(int op, int gdt, const Desc *descs, int count, const Sca
         case kFold: launch_gdt<kFold>(gdt, b, sc, stream); break;
         case kApply: launch_gdt<kApply>(gdt, b, sc, stream); break;
         case kFoldFirst: launch_gdt<kFoldFirst>(gdt, b, sc, stream); break;
+        case kFoldLastApply: launch_gdt<kFoldLastApply>(gdt, b, sc, stream); break;
         case kRescaleApply: launch_gdt<kRescaleApply>(gdt, b, sc, stream); break;
-        default: launch_gdt<kFoldLastApply>(gdt, b, sc, stream); break;
+        case kSgdDecay: launch_gdt<kSgdDecay>(gdt, b, sc, stream); break;
+        case kSgdFold: launch_gdt<kSgdFold>(gdt, b, sc, stream); break;
+        case kSgdApply: launch_gdt<kSgdApply>(gdt, b, sc, stream); break;
+        case kSgdFoldFirst: launch_gdt<kSgdFoldFirst>(gdt, b, sc, stream); break;
+        case kSgdFoldLastApply: launch_gdt<kSgdFoldLastApply>(gdt, b, sc, stream); break;
+        default: return fail(ADAMA_ERR_INVALID_ARG, "op = %d", op);
         }
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return fail(ADAMA_ERR_HIP, "kernel launch: %s", hipGetErrorString(e));
@@ -160,14 +166,43 @@ adama_status check_dtype(adama_dtype gdt)
 
 #define ADAMA_TRY(expr) do { adama_status st_ = (expr); if (st_ != ADAMA_OK) return st_; } while (0)
 
+adama_status check_list(int count, const void *list)
+{
+    if (count < 0) return fail(ADAMA_ERR_INVALID_ARG, "count = %d is negative", count);
+    if (count > 0 && !list) return fail(ADAMA_ERR_INVALID_ARG, "list is NULL with count = %d", count);
+    return ADAMA_OK;
+}
+
+adama_status check_micro_batches(int N)
+{
+    if (N < 1) return fail(ADAMA_ERR_INVALID_ARG, "N = %d: the number of micro-batches must be >= 1", N);
+    return ADAMA_OK;
+}
+
 adama_status check_fold_hyper(adama_dtype gdt, int count, const void *list, int N, double beta1, double beta2)
 {
     ADAMA_TRY(check_dtype(gdt));
-    if (count < 0) return fail(ADAMA_ERR_INVALID_ARG, "count = %d is negative", count);
-    if (count > 0 && !list) return fail(ADAMA_ERR_INVALID_ARG, "list is NULL with count = %d", count);
-    if (N < 1) return fail(ADAMA_ERR_INVALID_ARG, "N = %d: the number of micro-batches must be >= 1", N);
+    ADAMA_TRY(check_list(count, list));
+    ADAMA_TRY(check_micro_batches(N));
     if (!unit_interval(beta1) || !unit_interval(beta2))
         return fail(ADAMA_ERR_INVALID_ARG, "beta1 = %g, beta2 = %g must lie in [0, 1)", beta1, beta2);
+    return ADAMA_OK;
+}
+
+// The options of the variant calls; a NULL pointer selects no weight decay and a gradient scale of 1.
+struct Options {
+    double weight_decay = 0.0, grad_scale = 1.0;
+};
+
+adama_status read_options(const adama_options *opt, Options &out)
+{
+    if (!opt) return ADAMA_OK;
+    if (!finite_nonneg(opt->weight_decay))
+        return fail(ADAMA_ERR_INVALID_ARG, "weight_decay = %g must be finite and >= 0", opt->weight_decay);
+    if (!(std::isfinite(opt->grad_scale) && opt->grad_scale > 0.0))
+        return fail(ADAMA_ERR_INVALID_ARG, "grad_scale = %g must be finite and > 0", opt->grad_scale);
+    out.weight_decay = opt->weight_decay;
+    out.grad_scale = opt->grad_scale;
     return ADAMA_OK;
 }
 
@@ -201,8 +236,7 @@ adama_status check_update_args(const adama_update_tensor *list, int count, adama
 
 adama_status check_state_args(const adama_state *list, int count, bool need_theta)
 {
-    if (count < 0) return fail(ADAMA_ERR_INVALID_ARG, "count = %d is negative", count);
-    if (count > 0 && !list) return fail(ADAMA_ERR_INVALID_ARG, "list is NULL with count = %d", count);
+    ADAMA_TRY(check_list(count, list));
     for (int i = 0; i < count; ++i) {
         ADAMA_TRY(check_len(i, list[i].n));
         if (need_theta) ADAMA_TRY(check_array("theta", i, list[i].theta, 4, list[i].n));
@@ -225,11 +259,12 @@ adama_status check_apply_hyper(double lr, double eps, double beta1, double beta2
 // Descriptor lists are converted in pieces of this many tensors so that no call allocates.
 constexpr int kPiece = 4 * kMaxTensors;
 
-void set_fold_scalars(Scalars &sc, int N, double beta1, double beta2)
+// grad_scale == 1 leaves both constants exactly as (1-beta1)/N and (1-beta2)/N^2.
+void set_fold_scalars(Scalars &sc, int N, double beta1, double beta2, double grad_scale)
 {
     const double dn = (double)N;
-    sc.c1 = (float)((1.0 - beta1) / dn);
-    sc.c2 = (float)((1.0 - beta2) / (dn * dn));
+    sc.c1 = (float)((1.0 - beta1) * grad_scale / dn);
+    sc.c2 = (float)((1.0 - beta2) * (grad_scale * grad_scale) / (dn * dn));
 }
 
 void set_decay_scalars(Scalars &sc, double beta1, double beta2)
@@ -247,6 +282,21 @@ void set_apply_scalars(Scalars &sc, double lr, double eps, double beta1, double 
     sc.eps = (float)eps;
 }
 
+void set_weight_decay(Scalars &sc, double lr, double weight_decay) { sc.wd = (float)(lr * weight_decay); }
+
+adama_status check_sgdm_args(const adama_sgdm_tensor *list, int count, int op, adama_dtype gdt)
+{
+    ADAMA_TRY(check_list(count, list));
+    const size_t gb = gdt == ADAMA_F32 ? 4 : 2;
+    for (int i = 0; i < count; ++i) {
+        ADAMA_TRY(check_len(i, list[i].n));
+        if (op_updates(op)) ADAMA_TRY(check_array("theta", i, list[i].theta, 4, list[i].n));
+        ADAMA_TRY(check_array("b", i, list[i].b, 4, list[i].n));
+        if (op_has_grad(op)) ADAMA_TRY(check_array("grad", i, list[i].grad, gb, list[i].n));
+    }
+    return ADAMA_OK;
+}
+
 // Converts the caller's list piece by piece with `to_desc` and launches `op` over it.
 template <typename T, typename ToDesc>
 adama_status run_list(int op, int gdt, const T *list, int count, const Scalars &sc, hipStream_t stream, ToDesc &&to_desc)
@@ -262,12 +312,27 @@ adama_status run_list(int op, int gdt, const T *list, int count, const Scalars &
 
 Desc fold_desc(const adama_tensor &t) { return Desc{{t.m, t.v, nullptr}, t.grad, t.n}; }
 Desc update_desc(const adama_update_tensor &t) { return Desc{{t.theta, t.m, t.v}, t.grad, t.n}; }
+Desc state_desc(const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; }
 
-// The arrays op `op` uses, out of the superset descriptor of the geometry walk.
-Desc walk_desc(int op, const adama_update_tensor &t)
+// The arrays op `op` uses out of [theta,] m, v, grad: theta leads when the op updates it, the SGD ops
+// have no v, and ops without a fold ignore the gradient.
+Desc op_desc(int op, float *theta, float *m, float *v, const void *grad, size_t n)
 {
-    if (op_states(op) == 3) return Desc{{t.theta, t.m, t.v}, op_has_grad(op) ? t.grad : nullptr, t.n};
-    return Desc{{t.m, t.v, nullptr}, op_has_grad(op) ? t.grad : nullptr, t.n};
+    Desc d{{nullptr, nullptr, nullptr}, op_has_grad(op) ? grad : nullptr, n};
+    int k = 0;
+    if (op_updates(op)) d.s[k++] = theta;
+    d.s[k++] = m;
+    if (!op_is_sgd(op)) d.s[k++] = v;
+    return d;
+}
+
+Desc walk_desc(int op, const adama_update_tensor &t) { return op_desc(op, t.theta, t.m, t.v, t.grad, t.n); }
+
+adama_status run_sgdm(int op, adama_dtype gdt, const adama_sgdm_tensor *list, int count, const Scalars &sc,
+                      hipStream_t stream)
+{
+    return run_list(op, (int)gdt, list, count, sc, stream,
+                    [op](const adama_sgdm_tensor &t) { return op_desc(op, t.theta, t.b, nullptr, t.grad, t.n); });
 }
 
 }  // namespace
@@ -286,13 +351,21 @@ void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems
     if (policy_bits) *policy_bits = kNtPolicy;
 }
 
+adama_status adama_fold_opt_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                                  double beta2, const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2, o.grad_scale);
+    return run_list(kFold, (int)gdt, list, count, sc, stream, fold_desc);
+}
+
 adama_status adama_fold_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
                               double beta2, hipStream_t stream)
 {
-    ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
-    Scalars sc{};
-    set_fold_scalars(sc, N, beta1, beta2);
-    return run_list(kFold, (int)gdt, list, count, sc, stream, fold_desc);
+    return adama_fold_opt_multi(list, count, gdt, N, beta1, beta2, nullptr, stream);
 }
 
 adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N, double beta1,
@@ -302,14 +375,22 @@ adama_status adama_fold(float *m, float *v, const void *grad, adama_dtype gdt, s
     return adama_fold_multi(&one, 1, gdt, N, beta1, beta2, stream);
 }
 
+adama_status adama_fold_first_opt_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
+                                        double beta2, const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2, o.grad_scale);
+    set_decay_scalars(sc, beta1, beta2);
+    return run_list(kFoldFirst, (int)gdt, list, count, sc, stream, fold_desc);
+}
+
 adama_status adama_fold_first_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
                                     double beta2, hipStream_t stream)
 {
-    ADAMA_TRY(check_fold_args(list, count, gdt, N, beta1, beta2));
-    Scalars sc{};
-    set_fold_scalars(sc, N, beta1, beta2);
-    set_decay_scalars(sc, beta1, beta2);
-    return run_list(kFoldFirst, (int)gdt, list, count, sc, stream, fold_desc);
+    return adama_fold_first_opt_multi(list, count, gdt, N, beta1, beta2, nullptr, stream);
 }
 
 adama_status adama_fold_first(float *m, float *v, const void *grad, adama_dtype gdt, size_t n, int N,
@@ -319,16 +400,26 @@ adama_status adama_fold_first(float *m, float *v, const void *grad, adama_dtype 
     return adama_fold_first_multi(&one, 1, gdt, N, beta1, beta2, stream);
 }
 
+adama_status adama_fold_last_apply_opt_multi(const adama_update_tensor *list, int count, adama_dtype gdt, int N,
+                                             double lr, double eps, double beta1, double beta2, long long t,
+                                             const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_update_args(list, count, gdt, N, beta1, beta2));
+    ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    set_fold_scalars(sc, N, beta1, beta2, o.grad_scale);
+    set_apply_scalars(sc, lr, eps, beta1, beta2, t);
+    set_weight_decay(sc, lr, o.weight_decay);
+    return run_list(kFoldLastApply, (int)gdt, list, count, sc, stream, update_desc);
+}
+
 adama_status adama_fold_last_apply_multi(const adama_update_tensor *list, int count, adama_dtype gdt, int N,
                                          double lr, double eps, double beta1, double beta2, long long t,
                                          hipStream_t stream)
 {
-    ADAMA_TRY(check_update_args(list, count, gdt, N, beta1, beta2));
-    ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
-    Scalars sc{};
-    set_fold_scalars(sc, N, beta1, beta2);
-    set_apply_scalars(sc, lr, eps, beta1, beta2, t);
-    return run_list(kFoldLastApply, (int)gdt, list, count, sc, stream, update_desc);
+    return adama_fold_last_apply_opt_multi(list, count, gdt, N, lr, eps, beta1, beta2, t, nullptr, stream);
 }
 
 adama_status adama_fold_last_apply(float *theta, float *m, float *v, const void *grad, adama_dtype gdt,
@@ -357,29 +448,53 @@ adama_status adama_begin_step(float *m, float *v, size_t n, double beta1, double
     return adama_begin_step_multi(&one, 1, beta1, beta2, stream);
 }
 
-adama_status adama_apply_multi(const adama_state *list, int count, double lr, double eps, double beta1,
-                               double beta2, long long t, hipStream_t stream)
+adama_status adama_apply_opt_multi(const adama_state *list, int count, double lr, double eps, double beta1,
+                                   double beta2, long long t, const adama_options *opt, hipStream_t stream)
 {
     ADAMA_TRY(check_state_args(list, count, true));
     ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
     Scalars sc{};
     set_apply_scalars(sc, lr, eps, beta1, beta2, t);
-    return run_list(kApply, kF32, list, count, sc, stream,
-                    [](const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; });
+    set_weight_decay(sc, lr, o.weight_decay);
+    return run_list(kApply, kF32, list, count, sc, stream, state_desc);
 }
 
-adama_status adama_rescale_apply_multi(const adama_state *list, int count, double m_scale, double v_scale, double lr,
-                                       double eps, double beta1, double beta2, long long t, hipStream_t stream)
+adama_status adama_apply_multi(const adama_state *list, int count, double lr, double eps, double beta1,
+                               double beta2, long long t, hipStream_t stream)
+{
+    return adama_apply_opt_multi(list, count, lr, eps, beta1, beta2, t, nullptr, stream);
+}
+
+adama_status adama_apply(float *theta, const float *m, const float *v, size_t n, double lr, double eps,
+                         double beta1, double beta2, long long t, hipStream_t stream)
+{
+    adama_state one{theta, const_cast<float *>(m), const_cast<float *>(v), n};
+    return adama_apply_multi(&one, 1, lr, eps, beta1, beta2, t, stream);
+}
+
+adama_status adama_rescale_apply_opt_multi(const adama_state *list, int count, double m_scale, double v_scale,
+                                           double lr, double eps, double beta1, double beta2, long long t,
+                                           const adama_options *opt, hipStream_t stream)
 {
     ADAMA_TRY(check_state_args(list, count, true));
     ADAMA_TRY(check_apply_hyper(lr, eps, beta1, beta2, t));
     if (!finite_nonneg(m_scale) || !finite_nonneg(v_scale))
         return fail(ADAMA_ERR_INVALID_ARG, "m_scale = %g, v_scale = %g must be finite and >= 0", m_scale, v_scale);
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
     Scalars sc{};
     set_decay_scalars(sc, m_scale, v_scale);
     set_apply_scalars(sc, lr, eps, beta1, beta2, t);
-    return run_list(kRescaleApply, kF32, list, count, sc, stream,
-                    [](const adama_state &t) { return Desc{{t.theta, t.m, t.v}, nullptr, t.n}; });
+    set_weight_decay(sc, lr, o.weight_decay);
+    return run_list(kRescaleApply, kF32, list, count, sc, stream, state_desc);
+}
+
+adama_status adama_rescale_apply_multi(const adama_state *list, int count, double m_scale, double v_scale, double lr,
+                                       double eps, double beta1, double beta2, long long t, hipStream_t stream)
+{
+    return adama_rescale_apply_opt_multi(list, count, m_scale, v_scale, lr, eps, beta1, beta2, t, nullptr, stream);
 }
 
 adama_status adama_rescale_apply(float *theta, float *m, float *v, size_t n, double m_scale, double v_scale,
@@ -389,11 +504,71 @@ adama_status adama_rescale_apply(float *theta, float *m, float *v, size_t n, dou
     return adama_rescale_apply_multi(&one, 1, m_scale, v_scale, lr, eps, beta1, beta2, t, stream);
 }
 
-adama_status adama_apply(float *theta, const float *m, const float *v, size_t n, double lr, double eps,
-                         double beta1, double beta2, long long t, hipStream_t stream)
+// ---- SGD with momentum ----
+adama_status adama_sgdm_begin_step_multi(const adama_sgdm_tensor *list, int count, double momentum, hipStream_t stream)
 {
-    adama_state one{theta, const_cast<float *>(m), const_cast<float *>(v), n};
-    return adama_apply_multi(&one, 1, lr, eps, beta1, beta2, t, stream);
+    ADAMA_TRY(check_sgdm_args(list, count, kSgdDecay, ADAMA_F32));
+    if (!finite_nonneg(momentum)) return fail(ADAMA_ERR_INVALID_ARG, "momentum = %g must be finite and >= 0", momentum);
+    Scalars sc{};
+    sc.d1 = (float)momentum;
+    return run_sgdm(kSgdDecay, ADAMA_F32, list, count, sc, stream);
+}
+
+adama_status adama_sgdm_fold_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                   const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_dtype(gdt));
+    ADAMA_TRY(check_micro_batches(N));
+    ADAMA_TRY(check_sgdm_args(list, count, kSgdFold, gdt));
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    sc.c1 = (float)(o.grad_scale / (double)N);
+    return run_sgdm(kSgdFold, gdt, list, count, sc, stream);
+}
+
+adama_status adama_sgdm_fold_first_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                         double momentum, const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_dtype(gdt));
+    ADAMA_TRY(check_micro_batches(N));
+    ADAMA_TRY(check_sgdm_args(list, count, kSgdFoldFirst, gdt));
+    if (!finite_nonneg(momentum)) return fail(ADAMA_ERR_INVALID_ARG, "momentum = %g must be finite and >= 0", momentum);
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    sc.c1 = (float)(o.grad_scale / (double)N);
+    sc.d1 = (float)momentum;
+    return run_sgdm(kSgdFoldFirst, gdt, list, count, sc, stream);
+}
+
+adama_status adama_sgdm_apply_multi(const adama_sgdm_tensor *list, int count, double lr, const adama_options *opt,
+                                    hipStream_t stream)
+{
+    ADAMA_TRY(check_sgdm_args(list, count, kSgdApply, ADAMA_F32));
+    if (!std::isfinite(lr)) return fail(ADAMA_ERR_INVALID_ARG, "lr = %g is not finite", lr);
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    sc.step = (float)lr;
+    set_weight_decay(sc, lr, o.weight_decay);
+    return run_sgdm(kSgdApply, ADAMA_F32, list, count, sc, stream);
+}
+
+adama_status adama_sgdm_fold_last_apply_multi(const adama_sgdm_tensor *list, int count, adama_dtype gdt, int N,
+                                              double lr, const adama_options *opt, hipStream_t stream)
+{
+    ADAMA_TRY(check_dtype(gdt));
+    ADAMA_TRY(check_micro_batches(N));
+    ADAMA_TRY(check_sgdm_args(list, count, kSgdFoldLastApply, gdt));
+    if (!std::isfinite(lr)) return fail(ADAMA_ERR_INVALID_ARG, "lr = %g is not finite", lr);
+    Options o;
+    ADAMA_TRY(read_options(opt, o));
+    Scalars sc{};
+    sc.c1 = (float)(o.grad_scale / (double)N);
+    sc.step = (float)lr;
+    set_weight_decay(sc, lr, o.weight_decay);
+    return run_sgdm(kSgdFoldLastApply, gdt, list, count, sc, stream);
 }
 
 adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op, adama_dtype gdt,

@@ -29,15 +29,37 @@ constexpr int kMaxTensors = 80;   // descriptors per launch (table lives in the 
 // The steps of the path.  "First" folds perform the mini-batch's decay on the way (micro-batch 0),
 // "LastApply" folds perform the parameter update on the way (micro-batch N-1).  "RescaleApply" is the
 // update of the data-parallel scheme: the all-reduced moments are rescaled, written back, and used.
-enum Op : int { kDecay = 0, kFold = 1, kApply = 2, kFoldFirst = 3, kFoldLastApply = 4, kRescaleApply = 5, kNumOps = 6 };
+// The kSgd* ops are the same five steps for SGD with momentum, whose only moment is the buffer b.
+enum Op : int {
+    kDecay = 0, kFold = 1, kApply = 2, kFoldFirst = 3, kFoldLastApply = 4, kRescaleApply = 5,
+    kSgdDecay = 6, kSgdFold = 7, kSgdApply = 8, kSgdFoldFirst = 9, kSgdFoldLastApply = 10,
+    kNumOps = 11
+};
 
-// Number of float32 state arrays an op touches, and whether it reads a gradient.
-//   decay, fold, fold_first : s = {m, v}
-//   apply, fold_last_apply, rescale_apply : s = {theta, m, v}
-ADAMA_HD constexpr int op_states(int op) { return (op == kApply || op == kFoldLastApply || op == kRescaleApply) ? 3 : 2; }
-ADAMA_HD constexpr bool op_has_grad(int op) { return op == kFold || op == kFoldFirst || op == kFoldLastApply; }
-// Bit k set: state array k is written back.
-ADAMA_HD constexpr int op_store_mask(int op) { return op == kApply ? 1 : (op == kFoldLastApply || op == kRescaleApply) ? 7 : 3; }
+ADAMA_HD constexpr bool op_is_sgd(int op) { return op >= kSgdDecay && op <= kSgdFoldLastApply; }
+// The op scales the moments first (by beta1, beta2 / the momentum / the all-reduce factors).
+ADAMA_HD constexpr bool op_decays(int op)
+{
+    return op == kDecay || op == kFoldFirst || op == kRescaleApply || op == kSgdDecay || op == kSgdFoldFirst;
+}
+// The op reads a gradient and folds it into the moments.
+ADAMA_HD constexpr bool op_has_grad(int op)
+{
+    return op == kFold || op == kFoldFirst || op == kFoldLastApply || op == kSgdFold || op == kSgdFoldFirst ||
+           op == kSgdFoldLastApply;
+}
+// The op ends with the parameter update; theta is then state array 0 and the moments follow it.
+ADAMA_HD constexpr bool op_updates(int op)
+{
+    return op == kApply || op == kFoldLastApply || op == kRescaleApply || op == kSgdApply || op == kSgdFoldLastApply;
+}
+// Number of float32 state arrays an op touches: s = [theta,] m, v for the Adam ops, [theta,] b for the SGD ops.
+ADAMA_HD constexpr int op_states(int op) { return (op_updates(op) ? 1 : 0) + (op_is_sgd(op) ? 1 : 2); }
+// Bit k set: state array k is written back.  A plain update leaves the moments untouched.
+ADAMA_HD constexpr int op_store_mask(int op)
+{
+    return (op == kApply || op == kSgdApply) ? 1 : (1 << op_states(op)) - 1;
+}
 
 // The arrays of one tensor: up to three float32 state arrays and the gradient.
 struct Desc {

@@ -13,6 +13,10 @@
 //   fold_last_apply : read grad, theta, m, v    write theta, m, v   24 + sizeof(grad)
 //   rescale_apply   : read theta, m, v          write theta, m, v   24
 //
+// and the same five steps for SGD with momentum, which keeps one moment (the buffer b):
+//
+//   sgd decay 8, sgd fold / fold_first 8 + sizeof(grad), sgd apply 12, sgd fold_last_apply 16 + sizeof(grad)
+//
 // so the design goal is HBM bandwidth, not arithmetic: no MFMA, no LDS tiling of
 // data (there is no reuse), only wide coalesced accesses and enough of them in
 // flight.  A workgroup of 256 threads handles one chunk of 1024*U elements;
@@ -51,10 +55,12 @@ enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4 };
 
 // Per-launch scalars, already rounded to float32 from double on the host.
 //   c1 = (1-beta1)/N, c2 = (1-beta2)/N^2            fold, fold_first, fold_last_apply
-//   d1 = beta1, d2 = beta2                           decay, fold_first (rescale_apply: 1/M, 1/M^2)
-//   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply, rescale_apply
+//        (with a gradient scale s: c1 = (1-beta1) s/N, c2 = (1-beta2) (s/N)^2;  SGD: c1 = s/N)
+//   d1 = beta1, d2 = beta2                           decay, fold_first (rescale_apply: 1/M, 1/M^2;  SGD: d1 = momentum)
+//   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply, rescale_apply  (SGD: step = lr)
+//   wd = lr*lambda                                   decoupled weight decay of the updates; 0 = none
 struct Scalars {
-    float c1, c2, d1, d2, step, rs2, eps;
+    float c1, c2, d1, d2, step, rs2, eps, wd;
 };
 
 template <bool NT, typename T>
@@ -104,7 +110,7 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 };
 
 // ---- the arithmetic, one element at a time ----
-// s[] holds the element of each state array of the op (see op_states): {m, v} or {theta, m, v}.
+// s[] holds the element of each state array of the op (see op_states): [theta,] m, v or [theta,] b.
 // Every product and sum below is rounded on its own (contraction is off), so a fused edge form
 // produces the very bits the separate steps would.
 //
@@ -114,21 +120,34 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 //   apply  (Alg. 2, Update):                  theta <- theta - step*m / (sqrt(v)*rs2 + eps)
 //                                             = theta - lr*m_hat/(sqrt(v_hat)+eps); IEEE sqrt and divide
 //   rescale_apply (Sec. 3.3, after Eq. 5):    m <- m/M, v <- v/M^2 on the all-reduced sums, then apply
+//
+// Variants the paper's Conclusion points at (the same scheme for other momentum-based optimizers):
+//   decoupled weight decay:  theta <- theta - (lr*lambda*theta + Adam step); the two are summed first
+//                            so theta is rounded once.  With wd == 0 the plain expression is selected,
+//                            bit for bit.
+//   SGD with momentum:       b <- mu*b;  b <- b + c1*g;  theta <- theta - (lr*lambda*theta + lr*b)
 template <int OpK>
 __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars &sc)
 {
-    constexpr int im = op_states(OpK) == 3 ? 1 : 0, iv = im + 1;
-    if constexpr (OpK == kDecay || OpK == kFoldFirst || OpK == kRescaleApply) {
+    constexpr int im = op_updates(OpK) ? 1 : 0, iv = im + 1;
+    if constexpr (op_decays(OpK)) {
         s[im] = sc.d1 * s[im];
-        s[iv] = sc.d2 * s[iv];
+        if constexpr (!op_is_sgd(OpK)) s[iv] = sc.d2 * s[iv];
     }
     if constexpr (op_has_grad(OpK)) {
         s[im] = __builtin_fmaf(sc.c1, g, s[im]);
-        s[iv] = __builtin_fmaf(sc.c2, g * g, s[iv]);
+        if constexpr (!op_is_sgd(OpK)) s[iv] = __builtin_fmaf(sc.c2, g * g, s[iv]);
     }
-    if constexpr (OpK == kApply || OpK == kFoldLastApply || OpK == kRescaleApply) {
-        const float denom = __builtin_fmaf(__builtin_sqrtf(s[iv]), sc.rs2, sc.eps);
-        s[0] = s[0] - (sc.step * s[im]) / denom;
+    if constexpr (op_updates(OpK)) {
+        float delta;
+        if constexpr (op_is_sgd(OpK)) {
+            delta = sc.step * s[im];
+        } else {
+            const float denom = __builtin_fmaf(__builtin_sqrtf(s[iv]), sc.rs2, sc.eps);
+            delta = (sc.step * s[im]) / denom;
+        }
+        const float decayed = __builtin_fmaf(sc.wd, s[0], delta);
+        s[0] = s[0] - (sc.wd != 0.0f ? decayed : delta);
     }
 }
 
@@ -165,7 +184,9 @@ __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint3
         if constexpr (op_has_grad(OpK)) gf = G::widen(g[u]);
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
-            float e[3] = {x[0][u][j], x[1][u][j], NS == 3 ? x[NS - 1][u][j] : 0.0f};
+            float e[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int k = 0; k < NS; ++k) e[k] = x[k][u][j];
             element_op<OpK>(e, gf[j], sc);
 #pragma unroll
             for (int k = 0; k < NS; ++k) x[k][u][j] = e[k];
@@ -193,7 +214,9 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
         if constexpr (op_has_grad(OpK)) gf = G::widen(*global_ptr<typename G::Vec>(d.g, e * sizeof(typename G::Elem)));
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
-            float el[3] = {x[0][j], x[1][j], NS == 3 ? x[NS - 1][j] : 0.0f};
+            float el[3] = {0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int k = 0; k < NS; ++k) el[k] = x[k][j];
             element_op<OpK>(el, gf[j], sc);
 #pragma unroll
             for (int k = 0; k < NS; ++k) x[k][j] = el[k];

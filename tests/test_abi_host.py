@@ -21,12 +21,17 @@ def lib():
 
 
 def test_header_symbols_are_exported(lib):
-    text = open(os.path.join(ROOT, "include", "adama.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    names = set(re.findall(r"\b(adama_[a-z_]+)\s*\(", text))
-    assert {"adama_begin_step", "adama_fold", "adama_fold_multi", "adama_apply", "adama_last_error"} <= names
+    import glob
+
+    names = set()
+    for path in glob.glob(os.path.join(ROOT, "include", "*.h")):
+        text = re.sub(r"/\*.*?\*/", "", open(path).read(), flags=re.S)
+        names |= set(re.findall(r"\b(adama_[a-z_]+)\s*\(", text))
+    assert {"adama_begin_step", "adama_fold", "adama_fold_multi", "adama_apply", "adama_last_error",
+            "adama_fold_opt_multi", "adama_apply_opt_multi", "adama_sgdm_fold_multi"} <= names
+    assert len(names) >= 26
     for name in sorted(names):
-        assert hasattr(lib, name), f"{name} declared in include/adama.h but not exported"
+        assert hasattr(lib, name), f"{name} declared in include/*.h but not exported"
 
 
 def test_header_constants_match_library(lib):
@@ -147,6 +152,66 @@ def test_rescale_apply_validation(lib):
         assert text in ei.value.message
 
 
+def test_option_validation(lib):
+    """The *_opt calls: NULL options are accepted, bad ones are rejected before anything is queued."""
+    fold = [(FAKE, FAKE + (1 << 30), FAKE + (2 << 30), 100)]
+    upd = [(FAKE + (3 << 30), FAKE, FAKE + (1 << 30), FAKE + (2 << 30), 100)]
+    st = [(FAKE + (3 << 30), FAKE, FAKE + (1 << 30), 100)]
+    binding.adama_fold_opt_multi([], 0, "bf16", 4, 0.9, 0.999, None)
+    binding.adama_fold_first_opt_multi([], 0, "bf16", 4, 0.9, 0.999, (0.0, 1.0 / 1024))
+    binding.adama_fold_last_apply_opt_multi([], 0, "f16", 4, 1e-3, 1e-8, 0.9, 0.999, 1, binding.options(0.01, 0.5))
+    binding.adama_apply_opt_multi([], 0, 1e-3, 1e-8, 0.9, 0.999, 1, (0.01, 1.0))
+    binding.adama_rescale_apply_opt_multi([], 0, 0.5, 0.25, 1e-3, 1e-8, 0.9, 0.999, 1, (0.01, 1.0))
+    for bad, text in (((-0.1, 1.0), "weight_decay"), ((float("nan"), 1.0), "weight_decay"), ((0.0, 0.0), "grad_scale"),
+                      ((0.0, -2.0), "grad_scale"), ((0.0, float("inf")), "grad_scale")):
+        for call in (lambda o: binding.adama_fold_opt_multi(fold, None, "bf16", 4, 0.9, 0.999, o),
+                     lambda o: binding.adama_fold_first_opt_multi(fold, None, "bf16", 4, 0.9, 0.999, o),
+                     lambda o: binding.adama_fold_last_apply_opt_multi(upd, None, "bf16", 4, 1e-3, 1e-8, 0.9, 0.999, 1, o),
+                     lambda o: binding.adama_apply_opt_multi(st, None, 1e-3, 1e-8, 0.9, 0.999, 1, o),
+                     lambda o: binding.adama_rescale_apply_opt_multi(st, None, 0.5, 0.25, 1e-3, 1e-8, 0.9, 0.999, 1, o),
+                     lambda o: binding.adama_sgdm_fold_multi([(None, FAKE, FAKE + (1 << 30), 10)], None, "f32", 2, o),
+                     lambda o: binding.adama_sgdm_apply_multi([(FAKE, FAKE + (1 << 30), None, 10)], None, 0.1, o)):
+            with pytest.raises(binding.AdamaError) as ei:
+                call(bad)
+            assert ei.value.status == binding.ERR_INVALID_ARG and text in ei.value.message
+    # the other checks of the plain calls still apply
+    with pytest.raises(binding.AdamaError) as ei:
+        binding.adama_fold_opt_multi(fold, None, "bf16", 0, 0.9, 0.999, None)
+    assert "micro-batches" in ei.value.message
+    with pytest.raises(binding.AdamaError) as ei:
+        binding.adama_apply_opt_multi(st, None, 1e-3, 1e-8, 0.9, 0.999, 0, (0.1, 1.0))
+    assert "t >= 1" in ei.value.message
+
+
+def test_sgdm_validation(lib):
+    binding.adama_sgdm_begin_step_multi([], 0, 0.9)
+    binding.adama_sgdm_fold_multi([(None, None, None, 0)], None, "bf16", 4)
+    binding.adama_sgdm_fold_first_multi([], 0, "f16", 4, 0.9)
+    binding.adama_sgdm_apply_multi([], 0, 0.1)
+    binding.adama_sgdm_fold_last_apply_multi([], 0, "f32", 4, 0.1, (0.01, 0.5))
+    th, b, g = FAKE, FAKE + (1 << 30), FAKE + (2 << 30)
+    cases = [
+        (lambda: binding.adama_sgdm_begin_step_multi([(None, None, None, 8)], None, 0.9), "b is NULL"),
+        (lambda: binding.adama_sgdm_begin_step_multi([(None, b, None, 8)], None, -0.9), "momentum"),
+        (lambda: binding.adama_sgdm_begin_step_multi([(None, b, None, 8)], None, float("nan")), "momentum"),
+        (lambda: binding.adama_sgdm_fold_multi([(None, b, None, 8)], None, "bf16", 4), "grad is NULL"),
+        (lambda: binding.adama_sgdm_fold_multi([(None, b, g + 1, 8)], None, "bf16", 4), "not aligned"),
+        (lambda: binding.adama_sgdm_fold_multi([(None, b, g, 8)], None, "bf16", 0), "micro-batches"),
+        (lambda: binding.adama_sgdm_fold_multi([(None, b, g, 8)], None, 5, 4), "dtype"),
+        (lambda: binding.adama_sgdm_fold_first_multi([(None, b, g, 8)], None, "f32", 4, float("inf")), "momentum"),
+        (lambda: binding.adama_sgdm_apply_multi([(None, b, None, 8)], None, 0.1), "theta is NULL"),
+        (lambda: binding.adama_sgdm_apply_multi([(th, b, None, 8)], None, float("inf")), "lr"),
+        (lambda: binding.adama_sgdm_fold_last_apply_multi([(th, b, None, 8)], None, "f16", 4, 0.1), "grad is NULL"),
+        (lambda: binding.adama_sgdm_fold_last_apply_multi([(th, b, g, (1 << 40) + 1)], None, "f16", 4, 0.1), "MAX_ELEMS"),
+    ]
+    for call, text in cases:
+        with pytest.raises(binding.AdamaError) as ei:
+            call()
+        assert text in ei.value.message, (text, ei.value.message)
+    # an apply ignores the gradient field, a decay ignores theta and the gradient
+    assert lib.adama_sgdm_begin_step_multi(binding.sgdm_list([(None, None, None, 0)]), 1, 0.9, None) == binding.OK
+
+
 def test_begin_step_hyper_parameters(lib):
     with pytest.raises(binding.AdamaError):
         binding.adama_begin_step(FAKE, FAKE + 4096, 10, -0.5, 0.999)
@@ -187,7 +252,9 @@ def test_geometry_aligned_tensors_use_vector_accesses(lib, gdt, gb):
 
 
 @pytest.mark.parametrize("op,gdt,gb", [(0, "f32", 4), (1, "f32", 4), (1, "bf16", 2), (1, "f16", 2), (2, "f32", 4),
-                                       (3, "bf16", 2), (3, "f32", 4), (4, "f16", 2), (4, "f32", 4), (5, "f32", 4)])
+                                       (3, "bf16", 2), (3, "f32", 4), (4, "f16", 2), (4, "f32", 4), (5, "f32", 4),
+                                       (6, "f32", 4), (7, "bf16", 2), (7, "f32", 4), (8, "f32", 4), (9, "f16", 2),
+                                       (10, "bf16", 2), (10, "f32", 4)])
 def test_geometry_misaligned_and_large(lib, op, gdt, gb):
     rng = np.random.default_rng(2)
     entries = []
@@ -222,6 +289,8 @@ def test_geometry_many_tensors_split_into_launches(lib):
     assert launches == 3
     nvec, nsc, launches = _walk_and_check(entries, 4, "bf16")
     assert launches == 3
+    nvec, nsc, launches = _walk_and_check(entries, 10, "bf16")
+    assert launches == 3
 
 
 def test_geometry_walk_flags_nothing_on_workload_shapes(lib):
@@ -239,5 +308,5 @@ def test_geometry_walk_flags_nothing_on_workload_shapes(lib):
                                 FAKE + (2 << 36) + w.grad_bytes * goff, n))
                 off += n
                 goff += n
-            for op in (1, 3, 4):
+            for op in (1, 3, 4, 7, 9, 10):
                 _walk_and_check(entries, op, w.gdtype)
