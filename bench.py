@@ -1,13 +1,17 @@
 #!/usr/bin/env python3
 """Benchmark of the AdamA hot path (decay + N x per-layer fold + update) on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|c1]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c3|c2|c5|c4|c1] [--optimizer adama|adamw|sgdm]
 
 A "step" is one whole mini-batch of the workload through libadama: adama_begin_step over all state,
 then for each of the N micro-batches one adama_fold_multi launch per layer in backward order, then
 adama_apply.  All inputs (theta, m, v and one micro-batch's worth of per-layer gradients, each layer
 at its own address) are resident in HBM before the clock starts; the timed region contains only
 libadama launches.  Prints ONE JSON line.
+
+--optimizer selects the same pass for a variant: "adamw" (decoupled weight decay 0.01 in the update,
+same kernels and bytes) or "sgdm" (SGD with momentum 0.9 accumulated the same way: one moment, so
+8 B decay + N x (8 + gradient) B folds + 12 B update per parameter).  The default is the paper's AdamA.
 """
 from __future__ import annotations
 
@@ -24,12 +28,29 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 
 
-def algorithmic_bytes_per_step(w) -> int:
-    """decay 16 B/param + N folds of (16 + grad bytes) B/param + update 16 B/param."""
-    return (16 + w.N * (16 + w.grad_bytes) + 16) * w.P
+WEIGHT_DECAY = {"adama": 0.0, "adamw": 0.01, "sgdm": 0.0}
+MOMENTUM = 0.9
 
 
-def cpu_baseline(w, budget_s: float = 15.0) -> dict:
+def state_bytes(optimizer: str) -> int:
+    """Bytes per parameter a pass over the moments reads and writes: m, v (Adam) or b (SGD)."""
+    return 8 if optimizer == "sgdm" else 16
+
+
+def per_param_bytes(w, optimizer: str, fused: bool = False) -> int:
+    """Separate calls: decay (moments r+w) + N folds (moments r+w + gradient) + update (theta r+w + moments r).
+    Fused edges: no decay pass, and the update adds only theta r+w to the last fold."""
+    s = state_bytes(optimizer)
+    if fused:
+        return w.N * (s + w.grad_bytes) + 8
+    return s + w.N * (s + w.grad_bytes) + (8 + s // 2)
+
+
+def algorithmic_bytes_per_step(w, optimizer: str = "adama") -> int:
+    return per_param_bytes(w, optimizer) * w.P
+
+
+def cpu_baseline(w, budget_s: float = 15.0, optimizer: str = "adama") -> dict:
     """The fp64 oracle, as it stands, timed on this host over whole layers of the same workload
     (one full mini-batch each: decay, N folds, update) until about `budget_s` seconds are used."""
     import numpy as np
@@ -52,14 +73,23 @@ def cpu_baseline(w, budget_s: float = 15.0) -> dict:
             v = np.zeros(n)
             grads = [synth.fill_host(w.grad_spec(1, i, ti), w.gdtype, n) for i in range(min(w.N, 2))]
             t0 = time.perf_counter()
-            oracle.begin_step(m, v, w.beta1, w.beta2)
-            for i in range(w.N):
-                oracle.fold(m, v, grads[i % len(grads)], w.N, w.beta1, w.beta2, gdtype=gd)
-            oracle.apply(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1)
+            if optimizer == "sgdm":
+                oracle.sgdm_begin_step(m, MOMENTUM)
+                for i in range(w.N):
+                    oracle.sgdm_fold(m, grads[i % len(grads)], w.N, 1.0, gdtype=gd)
+                oracle.sgdm_apply(theta, m, w.lr, WEIGHT_DECAY[optimizer])
+            else:
+                oracle.begin_step(m, v, w.beta1, w.beta2)
+                for i in range(w.N):
+                    oracle.fold(m, v, grads[i % len(grads)], w.N, w.beta1, w.beta2, gdtype=gd)
+                if optimizer == "adamw":
+                    oracle.apply_adamw(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1, WEIGHT_DECAY[optimizer])
+                else:
+                    oracle.apply(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1)
             spent += time.perf_counter() - t0
             params += n
         layers_done.append(li)
-    per_param = 16 + w.N * (16 + w.grad_bytes) + 16
+    per_param = per_param_bytes(w, optimizer)
     return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "params_per_s": round(params / spent, 1),
             "sample": f"{len(layers_done)} whole layer(s) of {w.name} ({params} params), one full mini-batch "
@@ -72,6 +102,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=8)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="c3", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--optimizer", default="adama", choices=["adama", "adamw", "sgdm"],
+                    help="adama: the paper's method (default); adamw / sgdm: the same pass for the variants")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB copy kernel (the known-size reference for hardware traffic counters)")
     ap.add_argument("--graph", action="store_true",
@@ -95,7 +127,10 @@ def main() -> int:
         return 1
     binding.load()                      # fails loudly if libadama.so is missing
     w = configs.FULL[args.workload]()
-    hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model")
+    opt = args.optimizer
+    hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model",
+                           optimizer="sgdm" if opt == "sgdm" else "adam", momentum=MOMENTUM,
+                           weight_decay=WEIGHT_DECAY[opt])
     sh = hb.stream_handle
     # ---- resident inputs: theta0 and one micro-batch of gradients, every layer at its own address ----
     for t in w.tensors:
@@ -199,25 +234,30 @@ def main() -> int:
             one_step_fused()
         hb.synchronize()
         fused_ms = (time.perf_counter() - t1) / args.steps * 1e3
-        fused_bytes = (w.N * (16 + w.grad_bytes) + 8) * w.P       # no decay pass; the update adds theta r+w only
+        fused_bytes = per_param_bytes(w, opt, fused=True) * w.P
         fused = {"ms_per_step": round(fused_ms, 3), "bytes_per_step": fused_bytes,
                  "value": round(fused_bytes / (fused_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
                  "params_per_s": round(w.P / (fused_ms * 1e-3), 1),
-                 "note": "same results bit for bit; adama_fold_first_multi / adama_fold_last_apply_multi at the edges"}
+                 "note": "same results bit for bit; the fold_first / fold_last_apply entry points at the edges"}
 
     # ---- live per-launch timing of the dominant kernel, HIP events on the launch stream ----
     for _ in range(min(2, args.steps)):
         one_step(True)
     hb.synchronize()
     fold_ms = sum(e0.elapsed_time(e1) for e0, e1, _, _ in fold_events)
-    fold_bytes = sum(n for _, _, n, _ in fold_events) * (16 + w.grad_bytes)
+    fold_bytes = sum(n for _, _, n, _ in fold_events) * (state_bytes(opt) + w.grad_bytes)
     launches = sum(k for _, _, _, k in fold_events)
     achieved = fold_bytes / (fold_ms * 1e-3) / 1e9 if fold_ms > 0 else 0.0
 
-    step_bytes = algorithmic_bytes_per_step(w)
+    step_bytes = algorithmic_bytes_per_step(w, opt)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
+    metric = "AdamA fold+apply effective HBM GB/s (algorithmic bytes of decay + N folds + update per second)"
+    if opt != "adama":
+        metric = f"{opt} variant: " + metric
+    op_label = "sgd_fold" if opt == "sgdm" else "fold"
+    dom_chunk = binding.adama_launch_chunk(op_label, max((w.layer_elems(li) for li in big_layers), default=0))
     out = {
-        "metric": "AdamA fold+apply effective HBM GB/s (algorithmic bytes of decay + N folds + update per second)",
+        "metric": metric,
         "value": round(value, 1),
         "unit": "GB/s",
         "n_gpus": 1,
@@ -230,14 +270,14 @@ def main() -> int:
         "dtype": "f32" if w.gdtype == "f32" else f"f32 state, {w.gdtype} gradients",
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.P, "tensors": len(w.tensors), "layers": len(w.layers),
-                   "micro_batches": w.N, "grad_dtype": w.gdtype, "bytes_per_step": step_bytes,
+                   "optimizer": opt, "micro_batches": w.N, "grad_dtype": w.gdtype, "bytes_per_step": step_bytes,
                    "fold_launches_per_step": w.N * len(w.layers)},
         "params_per_s": round(w.P / (ms_per_step * 1e-3), 1),
         "param_folds_per_s": round(w.P * w.N / (ms_per_step * 1e-3), 1),
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": f"multi_tensor_kernel<fold,{w.gdtype},U={tune['u_big']},policy={tune['policy_bits']},multi-tensor>",
+                     "kernel": f"multi_tensor_kernel<{op_label},{w.gdtype},U={dom_chunk // 1024},policy={tune['policy_bits']},multi-tensor>",
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},
@@ -247,12 +287,12 @@ def main() -> int:
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
                         "whole_model_bytes": w.P * w.grad_bytes},
     }
-    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json")
+    traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json" if opt != "sgdm" else f"traffic_{w.name}_sgdm.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as fh:
             out["roofline"]["traffic"] = json.load(fh).get("bytes_per_launch")
     if args.cpu_budget > 0:
-        out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget)
+        out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget, opt)
     print(json.dumps(out), flush=True)
     return 0
 

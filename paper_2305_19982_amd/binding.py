@@ -112,6 +112,8 @@ def load() -> ctypes.CDLL:
     lib.adama_last_error.argtypes = []
     lib.adama_max_tensors_per_launch.restype = i32
     lib.adama_max_tensors_per_launch.argtypes = []
+    lib.adama_launch_chunk.restype = i32
+    lib.adama_launch_chunk.argtypes = [i32, ctypes.c_ulonglong]
     lib.adama_tuning.restype = None
     lib.adama_tuning.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_ulonglong),
                                  ctypes.POINTER(i32)]
@@ -138,6 +140,14 @@ def adama_last_error() -> str:
 
 def adama_max_tensors_per_launch() -> int:
     return int(load().adama_max_tensors_per_launch())
+
+
+OPS = {"decay": 0, "fold": 1, "apply": 2, "fold_first": 3, "fold_last_apply": 4, "rescale_apply": 5,
+       "sgd_decay": 6, "sgd_fold": 7, "sgd_apply": 8, "sgd_fold_first": 9, "sgd_fold_last_apply": 10}
+
+
+def adama_launch_chunk(op, launch_elems: int) -> int:
+    return int(load().adama_launch_chunk(OPS.get(op, op), int(launch_elems)))
 
 
 def adama_tuning() -> dict:

@@ -34,11 +34,34 @@ adama_status fail(adama_status st, const char *fmt, ...)
 
 // ---- tuning constants (measured on MI355X with a sweep over U, grid shape and cache policy) ----
 constexpr int kUSmall = 1;                    // chunk = 1024 elements: many workgroups for small launches
-constexpr int kUBig = 4;                      // chunk = 4096 elements: 8..12 16-byte loads in flight per thread
+// Groups per thread per chunk by op (index = Op) for launches of at least kBigLaunchElems elements, and
+// for launches of at least kHugeLaunchElems.  Measured per op on whole transformer blocks (12.6 M .. 315 M
+// elements per launch) and on whole-state lists: the folds, which have the most independent streams, do
+// best with 2 groups (2048-element chunks, 6 16-byte loads in flight per thread) up to about 64 M elements
+// per launch (+1.5 % over 4 groups: twice as many workgroups fill the last partial wave of the grid
+// better) and with 4 groups from about 120 M elements on (+0.5..1.5 %); the first-micro-batch form was
+// repeatably 1..2 % faster with 4 at every size; everything that ends in the update, and the plain
+// decay, do best with 1 (+6..9 % for the update, whose three read streams and long dependent arithmetic
+// leave the fewest registers for loads in flight); the single-moment SGD ops with 2.
+#ifndef ADAMA_U_BIG_TABLE
+#define ADAMA_U_BIG_TABLE {1, 2, 1, 4, 1, 1, 2, 2, 2, 2, 2}
+#endif
+#ifndef ADAMA_U_HUGE_TABLE
+#define ADAMA_U_HUGE_TABLE {1, 4, 1, 4, 1, 1, 2, 2, 2, 2, 2}
+#endif
+constexpr int kUBigOf[kNumOps] = ADAMA_U_BIG_TABLE;
+constexpr int kUHugeOf[kNumOps] = ADAMA_U_HUGE_TABLE;
+constexpr int kUBig = kUBigOf[kFold];
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
-constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long use kUBig
+constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long use kUBigOf[op]
+constexpr uint64_t kHugeLaunchElems = 3u << 25;  // 100.7 M elements: launches at least this long use kUHugeOf[op]
+
+int launch_u_for(int op, uint64_t elems)
+{
+    return elems >= kHugeLaunchElems ? kUHugeOf[op] : elems >= kBigLaunchElems ? kUBigOf[op] : kUSmall;
+}
 // One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
 // a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
@@ -54,7 +77,7 @@ struct Batch {
 
 // Cuts descs[0..count) into launches.  Calls emit(batch, index of its first tensor) for each; stops at the first failure.
 template <typename Emit>
-adama_status for_each_batch(const Desc *descs, int count, Emit &&emit)
+adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
 {
     int i = 0;
     while (i < count) {
@@ -67,7 +90,7 @@ adama_status for_each_batch(const Desc *descs, int count, Emit &&emit)
             elems += descs[i + k].n;
             ++k;
         }
-        b.u = elems >= kBigLaunchElems ? kUBig : kUSmall;
+        b.u = launch_u_for(op, elems);
         const uint32_t chunk = kBlock * kGroup * b.u;
         uint64_t start = 0;
         for (int j = 0; j < k; ++j) {
@@ -101,8 +124,9 @@ void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
 template <int OpK, int GT>
 void launch_u(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
-    if (b.u == kUBig) launch_one<OpK, GT, kUBig>(b, sc, stream);
-    else launch_one<OpK, GT, kUSmall>(b, sc, stream);
+    if (b.u == kUSmall) launch_one<OpK, GT, kUSmall>(b, sc, stream);
+    else if (b.u == kUBigOf[OpK]) launch_one<OpK, GT, kUBigOf[OpK]>(b, sc, stream);
+    else launch_one<OpK, GT, kUHugeOf[OpK]>(b, sc, stream);
 }
 
 template <int OpK>
@@ -116,7 +140,7 @@ void launch_gdt(int gdt, const Batch &b, const Scalars &sc, hipStream_t stream)
 
 adama_status launch_all(int op, int gdt, const Desc *descs, int count, const Scalars &sc, hipStream_t stream)
 {
-    return for_each_batch(descs, count, [&](const Batch &b, int) -> adama_status {
+    return for_each_batch(op, descs, count, [&](const Batch &b, int) -> adama_status {
         switch (op) {
         case kDecay: launch_gdt<kDecay>(gdt, b, sc, stream); break;
         case kFold: launch_gdt<kFold>(gdt, b, sc, stream); break;
@@ -342,6 +366,12 @@ extern "C" {
 const char *adama_last_error(void) { return g_error; }
 
 int adama_max_tensors_per_launch(void) { return kMaxTensors; }
+
+int adama_launch_chunk(int op, unsigned long long launch_elems)
+{
+    if (op < 0 || op >= kNumOps) return 0;
+    return kBlock * kGroup * launch_u_for(op, launch_elems);
+}
 
 void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits)
 {
@@ -586,7 +616,7 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
         const int kp = count - i0 < kPiece ? count - i0 : kPiece;
         Desc piece[kPiece];
         for (int j = 0; j < kp; ++j) piece[j] = walk_desc(op, list[i0 + j]);
-        adama_status st = for_each_batch(piece, kp, [&](const Batch &b, int first) -> adama_status {
+        adama_status st = for_each_batch(op, piece, kp, [&](const Batch &b, int first) -> adama_status {
             ++nlaunch;
             const uint32_t chunk = kBlock * kGroup * b.u;
             const uint32_t cnt = b.tab.count;

@@ -39,14 +39,26 @@ class SimulatedBackward:
                    "model"    -> every layer has its own region (what gradient accumulation must keep);
                                  only for measurements that want all gradient inputs resident and
                                  distinct in HBM before the clock starts
+    optimizer    : "adam"     -> AdamA as in the paper (moments m, v)
+                   "sgdm"     -> SGD with momentum accumulated the same way (one moment, kept in the m
+                                 arena; no v arena is allocated).  The beta1/beta2/eps arguments of the
+                                 step methods are then ignored and `momentum` is used for the decay.
+    weight_decay, grad_scale : decoupled weight decay of the update and the factor applied to every
+                   gradient read (1/loss_scale); the defaults select the plain calls.
     """
 
     def __init__(self, tensor_sizes: Sequence[int], layers: Sequence[Sequence[int]], gdtype: str,
                  device: str = "cuda:0", stream: torch.cuda.Stream | None = None, pack: str = "aligned",
-                 grad_buffer: str = "layer"):
+                 grad_buffer: str = "layer", optimizer: str = "adam", momentum: float = 0.9,
+                 weight_decay: float = 0.0, grad_scale: float = 1.0):
         if gdtype not in _GRAD_BYTES:
             raise ValueError(gdtype)
+        if optimizer not in ("adam", "sgdm"):
+            raise ValueError(optimizer)
         binding.load()
+        self.optimizer = optimizer
+        self.momentum = float(momentum)
+        self._opt = None if (weight_decay == 0.0 and grad_scale == 1.0) else binding.options(weight_decay, grad_scale)
         self.device = torch.device(device)
         self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
         self.gdtype = gdtype
@@ -65,7 +77,8 @@ class SimulatedBackward:
         with torch.cuda.stream(self.stream):
             self.theta = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
             self.m = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-            self.v = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+            self.v = (torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+                      if optimizer == "adam" else None)
         # ---- the one gradient buffer: layer-local offsets, reused by every layer ----
         self.grad_offset = [0] * len(self.sizes)             # element offset inside the buffer
         largest = 0
@@ -80,8 +93,16 @@ class SimulatedBackward:
         self.grad_buffer_elems = max(largest, 1)
         self.grad_buffer = torch.empty(self.grad_buffer_elems * self.gbytes, dtype=torch.uint8, device=self.device)
         # ---- descriptor lists, built once ----
-        base_t, base_m, base_v = self.theta.data_ptr(), self.m.data_ptr(), self.v.data_ptr()
         gb = self.grad_buffer.data_ptr()
+        if optimizer == "sgdm":
+            base_t, base_b = self.theta.data_ptr(), self.m.data_ptr()
+            self._sgdm_lists = [binding.sgdm_list(
+                [(base_t + 4 * self.offset[ti], base_b + 4 * self.offset[ti],
+                  gb + self.gbytes * self.grad_offset[ti], self.sizes[ti]) for ti in idx]) for idx in self.layers]
+            self._sgdm_state = binding.sgdm_list(
+                [(base_t + 4 * o, base_b + 4 * o, None, n) for o, n in zip(self.offset, self.sizes)])
+            return
+        base_t, base_m, base_v = self.theta.data_ptr(), self.m.data_ptr(), self.v.data_ptr()
         self._fold_lists = []
         for idx in self.layers:
             self._fold_lists.append(binding.tensor_list(
@@ -118,17 +139,26 @@ class SimulatedBackward:
         return self.theta.data_ptr() + 4 * self.offset[ti]
 
     def tensor_view(self, which: str, ti: int) -> torch.Tensor:
-        arena = {"theta": self.theta, "m": self.m, "v": self.v}[which]
+        arena = {"theta": self.theta, "m": self.m, "b": self.m, "v": self.v}[which]
         return arena[self.offset[ti]: self.offset[ti] + self.sizes[ti]]
 
     # ---- Alg. 2 ----
     def begin_step(self, beta1: float, beta2: float) -> None:
         """t <- t+1, m <- beta1 m, v <- beta2 v."""
         self.t += 1
-        binding.adama_begin_step_multi(self._state_list, None, beta1, beta2, self.stream_handle)
+        if self.optimizer == "sgdm":
+            binding.adama_sgdm_begin_step_multi(self._sgdm_state, None, self.momentum, self.stream_handle)
+        else:
+            binding.adama_begin_step_multi(self._state_list, None, beta1, beta2, self.stream_handle)
 
     def fold_layer(self, li: int, N: int, beta1: float, beta2: float) -> None:
-        binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+        if self.optimizer == "sgdm":
+            binding.adama_sgdm_fold_multi(self._sgdm_lists[li], None, self.gdtype, N, self._opt, self.stream_handle)
+        elif self._opt is None:
+            binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+        else:
+            binding.adama_fold_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt,
+                                         self.stream_handle)
 
     # ---- the same mini-batch with the decay and the update riding along with the edge folds ----
     def begin_step_fused(self) -> None:
@@ -137,12 +167,27 @@ class SimulatedBackward:
 
     def fold_layer_first(self, li: int, N: int, beta1: float, beta2: float) -> None:
         """Micro-batch 0: decay + fold of layer li in one pass (Alg. 1's one-statement form)."""
-        binding.adama_fold_first_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+        if self.optimizer == "sgdm":
+            binding.adama_sgdm_fold_first_multi(self._sgdm_lists[li], None, self.gdtype, N, self.momentum, self._opt,
+                                                self.stream_handle)
+        elif self._opt is None:
+            binding.adama_fold_first_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2,
+                                           self.stream_handle)
+        else:
+            binding.adama_fold_first_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt,
+                                               self.stream_handle)
 
     def fold_layer_last_apply(self, li: int, N: int, lr: float, eps: float, beta1: float, beta2: float) -> None:
         """Micro-batch N-1: fold + parameter update of layer li in one pass."""
-        binding.adama_fold_last_apply_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1, beta2,
-                                            self.t, self.stream_handle)
+        if self.optimizer == "sgdm":
+            binding.adama_sgdm_fold_last_apply_multi(self._sgdm_lists[li], None, self.gdtype, N, lr, self._opt,
+                                                     self.stream_handle)
+        elif self._opt is None:
+            binding.adama_fold_last_apply_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1, beta2,
+                                                self.t, self.stream_handle)
+        else:
+            binding.adama_fold_last_apply_opt_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1,
+                                                    beta2, self.t, self._opt, self.stream_handle)
 
     def mini_batch_fused(self, produce: Callable[[int, int], None], N: int, lr: float, eps: float, beta1: float,
                          beta2: float) -> None:
@@ -169,7 +214,13 @@ class SimulatedBackward:
             self.fold_layer(li, N, beta1, beta2)
 
     def apply(self, lr: float, eps: float, beta1: float, beta2: float) -> None:
-        binding.adama_apply_multi(self._state_list, None, lr, eps, beta1, beta2, self.t, self.stream_handle)
+        if self.optimizer == "sgdm":
+            binding.adama_sgdm_apply_multi(self._sgdm_state, None, lr, self._opt, self.stream_handle)
+        elif self._opt is None:
+            binding.adama_apply_multi(self._state_list, None, lr, eps, beta1, beta2, self.t, self.stream_handle)
+        else:
+            binding.adama_apply_opt_multi(self._state_list, None, lr, eps, beta1, beta2, self.t, self._opt,
+                                          self.stream_handle)
 
     def mini_batch(self, produce: Callable[[int, int], None], N: int, lr: float, eps: float, beta1: float,
                    beta2: float) -> None:

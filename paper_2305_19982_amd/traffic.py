@@ -37,8 +37,16 @@ def main() -> None:
     ap.add_argument("--fetch", required=True)
     ap.add_argument("--write", required=True)
     ap.add_argument("--workload", required=True)
-    ap.add_argument("--kernel", default=r"multi_tensor_kernel<1, \d, 4, \d+, false>", help="regex of the dominant kernel's name")
+    ap.add_argument("--kernel", default=None,
+                    help="regex of the dominant kernel's name (default: the multi-tensor fold with the chunk size the "
+                         "built library uses for --launch-elems)")
+    ap.add_argument("--launch-elems", type=int, default=30_740_800, help="elements per launch of the dominant kernel")
     args = ap.parse_args()
+    if args.kernel is None:
+        from . import binding
+
+        u = binding.adama_launch_chunk("fold", args.launch_elems) // 1024
+        args.kernel = rf"multi_tensor_kernel<1, \d, {u}, \d+, false>"
     out = {"workload": args.workload, "unit": "bytes"}
     per_launch = {}
     for name, path, counter in (("fetch", args.fetch, "FETCH_SIZE"), ("write", args.write, "WRITE_SIZE")):

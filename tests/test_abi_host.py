@@ -267,13 +267,32 @@ def test_geometry_misaligned_and_large(lib, op, gdt, gb):
         c = FAKE + (2 << 36) + (i << 24) + gb * pre
         th = FAKE + (6 << 36) + (i << 24) + 4 * (pre if (co or i % 3) else (pre + 2) % 4)
         entries.append((th, a, b, c, n))
-    # one launch big enough for the 4096-element chunks, with every misalignment
+    # one launch big enough for the larger chunks of long launches, with every misalignment
     for pre in range(4):
         n = (1 << 22) + 3 * pre + 1
         entries.append((FAKE + (7 << 36) + (pre << 28) + 4 * pre, FAKE + (3 << 36) + (pre << 28) + 4 * pre,
                         FAKE + (4 << 36) + (pre << 28) + 4 * pre, FAKE + (5 << 36) + (pre << 28) + gb * pre, n))
     nvec, nsc, launches = _walk_and_check(entries, op, gdt)
     assert launches == 1 and nvec > 0 and nsc > 0
+
+
+def test_geometry_chunk_size_follows_launch_size(lib):
+    """Short launches use 1024-element chunks; the fold moves to larger chunks as launches grow."""
+    sizes = {n: binding.adama_launch_chunk("fold", n) for n in (1, (1 << 20) - 1, 1 << 20, 30_740_800, 3 << 25, 1 << 30)}
+    assert sizes[1] == sizes[(1 << 20) - 1] == 1024
+    assert sizes[1 << 20] == sizes[30_740_800] and sizes[3 << 25] == sizes[1 << 30]
+    assert 1024 < sizes[1 << 20] <= sizes[3 << 25]
+    assert binding.adama_launch_chunk(99, 5) == 0
+    for op in range(11):
+        for n in (5, 1 << 22, 1 << 28):
+            assert binding.adama_launch_chunk(op, n) in (1024, 2048, 4096)
+    # one launch past the upper threshold, misaligned start: every element once, in bounds
+    n = (3 << 25) + 5
+    entries = [(FAKE + (3 << 40) + 12, FAKE + 12, FAKE + (1 << 40) + 12, FAKE + (2 << 40) + 6, n)]
+    touched, nvec, nsc, launches = binding.adama_debug_walk(entries, 1, "bf16")
+    arr = np.frombuffer(touched[0], dtype=np.uint8)
+    assert arr.size == n and arr.min() == 1 and arr.max() == 1 and launches == 1
+    assert nvec * 4 + nsc == n and nsc <= 6
 
 
 def test_geometry_many_tensors_split_into_launches(lib):

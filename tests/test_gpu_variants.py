@@ -11,7 +11,7 @@ pytestmark = pytest.mark.gpu
 
 B1, B2, LR, EPS = 0.9, 0.999, 1e-3, 1e-8
 # two ragged lists packed back to back (every misalignment occurs): one short enough for the
-# 1024-element chunks, one long enough for the 4096-element chunks
+# 1024-element chunks, one long enough for the larger chunks of long launches
 SMALL = [0, 1, 2, 3, 5, 64, 1023, 1024, 1025, 4097, 12289, 0, 70001]
 BIG = [7, 300001, (1 << 22) + 77, 0, 4096 * 3 + 1, 65536, 9]
 
