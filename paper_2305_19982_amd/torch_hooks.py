@@ -33,26 +33,22 @@ def leaf_layers(module: torch.nn.Module) -> list:
     return layers
 
 
-class AdamAccumulation:
-    """Adam Accumulation driven by backward hooks.
+class _HookedAccumulation:
+    """Layer bookkeeping shared by the hooked optimizers: count down each layer's gradients inside the
+    backward pass, fold the layer with one launch when the last one has arrived, release the gradients.
 
-    layers : groups of parameters folded by one launch each (e.g. leaf_layers(model), or one group per
-             transformer block); every trainable parameter must appear in exactly one group
-    N      : micro-batches per mini-batch; the loss of each micro-batch is NOT divided by N by the caller
-             (the fold applies 1/N, as in Alg. 2)
+    Subclasses provide the state (`_alloc_state`) and the three kinds of launches (`_decay_all`,
+    `_fold`, `_apply_all`)."""
 
-    Per mini-batch:  begin_mini_batch();  N x (forward; loss.backward());  step()
-    """
-
-    def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-3,
-                 betas: tuple = (0.9, 0.999), eps: float = 1e-8, N: int = 1, fused_edges: bool = True):
+    def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], N: int, fused_edges: bool,
+                 weight_decay: float, grad_scale: float):
         binding.load()
-        self.lr, self.beta1, self.beta2, self.eps, self.N = float(lr), float(betas[0]), float(betas[1]), float(eps), int(N)
+        self.N = int(N)
         self.fused_edges = bool(fused_edges) and self.N > 1
+        self._opt = None if (weight_decay == 0.0 and grad_scale == 1.0) else binding.options(weight_decay, grad_scale)
         self.t = 0
         self.micro = 0
         self.layers = [list(ps) for ps in layers]
-        self.m, self.v = {}, {}
         self._layer_of = {}
         self._pending = []
         self._handles = []
@@ -66,22 +62,18 @@ class AdamAccumulation:
                 seen.add(id(p))
                 if p.dtype != torch.float32 or not p.is_cuda or not p.is_contiguous():
                     raise ValueError("parameters must be contiguous float32 CUDA tensors")
-                self.m[p] = torch.zeros_like(p)
-                self.v[p] = torch.zeros_like(p)
+                self._alloc_state(p)
                 self._layer_of[p] = li
                 self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
             self._pending.append(len(ps))
-        self._state_list = binding.state_list(
-            [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel()) for ps in self.layers for p in ps])
 
-    # ---- Alg. 2 ----
+    # ---- the mini-batch protocol ----
     def begin_mini_batch(self) -> None:
         """t <- t+1 and the moment decay (deferred into the first micro-batch's folds when fused)."""
         self.t += 1
         self.micro = 0
         if not self.fused_edges:
-            binding.adama_begin_step_multi(self._state_list, None, self.beta1, self.beta2,
-                                           torch.cuda.current_stream().cuda_stream)
+            self._decay_all(torch.cuda.current_stream().cuda_stream)
 
     def _on_grad(self, p: torch.nn.Parameter) -> None:
         li = self._layer_of[p]
@@ -97,17 +89,9 @@ class AdamAccumulation:
         gdt = _GDT[grads[0].dtype]
         if any(g.dtype != grads[0].dtype for g in grads):
             raise ValueError("gradients of one layer must share a dtype")
-        stream = torch.cuda.current_stream().cuda_stream
         first = self.fused_edges and self.micro == 0
         last = self.fused_edges and self.micro == self.N - 1
-        if last:
-            binding.adama_fold_last_apply_multi(
-                [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel())
-                 for p, g in zip(ps, grads)], None, gdt, self.N, self.lr, self.eps, self.beta1, self.beta2, self.t, stream)
-        else:
-            entries = [(self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
-            fn = binding.adama_fold_first_multi if first else binding.adama_fold_multi
-            fn(entries, None, gdt, self.N, self.beta1, self.beta2, stream)
+        self._fold(ps, grads, gdt, first, last, torch.cuda.current_stream().cuda_stream)
         for p in ps:                                   # release: the fold is queued on the producing stream
             self._live_grad_bytes -= p.grad.numel() * p.grad.element_size()
             p.grad = None
@@ -120,14 +104,91 @@ class AdamAccumulation:
         self.micro += 1
 
     def step(self) -> None:
-        """The bias-corrected update (already done by the last micro-batch's folds when fused)."""
+        """The parameter update (already done by the last micro-batch's folds when fused)."""
         if self.micro != self.N:
             raise RuntimeError(f"step() after {self.micro} of {self.N} micro-batches")
         if not self.fused_edges:
-            binding.adama_apply_multi(self._state_list, None, self.lr, self.eps, self.beta1, self.beta2, self.t,
-                                      torch.cuda.current_stream().cuda_stream)
+            self._apply_all(torch.cuda.current_stream().cuda_stream)
 
     def remove_hooks(self) -> None:
         for h in self._handles:
             h.remove()
         self._handles = []
+
+
+class AdamAccumulation(_HookedAccumulation):
+    """Adam Accumulation driven by backward hooks.
+
+    layers : groups of parameters folded by one launch each (e.g. leaf_layers(model), or one group per
+             transformer block); every trainable parameter must appear in exactly one group
+    N      : micro-batches per mini-batch; the loss of each micro-batch is NOT divided by N by the caller
+             (the fold applies 1/N, as in Alg. 2)
+    weight_decay : decoupled (AdamW); grad_scale : factor on every gradient read, 1/loss_scale when the
+             caller scaled the loss up.  The defaults are the paper's plain AdamA.
+
+    Per mini-batch:  begin_mini_batch();  N x (forward; loss.backward(); micro_batch_done());  step()
+    """
+
+    def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-3,
+                 betas: tuple = (0.9, 0.999), eps: float = 1e-8, N: int = 1, fused_edges: bool = True,
+                 weight_decay: float = 0.0, grad_scale: float = 1.0):
+        self.lr, self.beta1, self.beta2, self.eps = float(lr), float(betas[0]), float(betas[1]), float(eps)
+        self.m, self.v = {}, {}
+        super().__init__(layers, N, fused_edges, weight_decay, grad_scale)
+        self._state_list = binding.state_list(
+            [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel()) for ps in self.layers for p in ps])
+
+    def _alloc_state(self, p) -> None:
+        self.m[p] = torch.zeros_like(p)
+        self.v[p] = torch.zeros_like(p)
+
+    def _decay_all(self, stream: int) -> None:
+        binding.adama_begin_step_multi(self._state_list, None, self.beta1, self.beta2, stream)
+
+    def _fold(self, ps, grads, gdt, first: bool, last: bool, stream: int) -> None:
+        if last:
+            binding.adama_fold_last_apply_opt_multi(
+                [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel())
+                 for p, g in zip(ps, grads)], None, gdt, self.N, self.lr, self.eps, self.beta1, self.beta2, self.t,
+                self._opt, stream)
+            return
+        entries = [(self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
+        fn = binding.adama_fold_first_opt_multi if first else binding.adama_fold_opt_multi
+        fn(entries, None, gdt, self.N, self.beta1, self.beta2, self._opt, stream)
+
+    def _apply_all(self, stream: int) -> None:
+        binding.adama_apply_opt_multi(self._state_list, None, self.lr, self.eps, self.beta1, self.beta2, self.t,
+                                      self._opt, stream)
+
+
+class MomentumAccumulation(_HookedAccumulation):
+    """SGD with momentum accumulated the AdamA way (the paper's Conclusion): the momentum buffer takes
+    each layer's gradient of each micro-batch as it is produced, and the gradient is released.  The
+    result is the textbook step b <- mu b + mean gradient, theta <- theta - lr b (plus decoupled weight
+    decay, if any) up to rounding.  Protocol and arguments as AdamAccumulation."""
+
+    def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-2, momentum: float = 0.9,
+                 N: int = 1, fused_edges: bool = True, weight_decay: float = 0.0, grad_scale: float = 1.0):
+        self.lr, self.momentum = float(lr), float(momentum)
+        self.b = {}
+        super().__init__(layers, N, fused_edges, weight_decay, grad_scale)
+        self._state_list = binding.sgdm_list(
+            [(p.data_ptr(), self.b[p].data_ptr(), None, p.numel()) for ps in self.layers for p in ps])
+
+    def _alloc_state(self, p) -> None:
+        self.b[p] = torch.zeros_like(p)
+
+    def _decay_all(self, stream: int) -> None:
+        binding.adama_sgdm_begin_step_multi(self._state_list, None, self.momentum, stream)
+
+    def _fold(self, ps, grads, gdt, first: bool, last: bool, stream: int) -> None:
+        entries = [(p.data_ptr(), self.b[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
+        if last:
+            binding.adama_sgdm_fold_last_apply_multi(entries, None, gdt, self.N, self.lr, self._opt, stream)
+        elif first:
+            binding.adama_sgdm_fold_first_multi(entries, None, gdt, self.N, self.momentum, self._opt, stream)
+        else:
+            binding.adama_sgdm_fold_multi(entries, None, gdt, self.N, self._opt, stream)
+
+    def _apply_all(self, stream: int) -> None:
+        binding.adama_sgdm_apply_multi(self._state_list, None, self.lr, self._opt, stream)

@@ -125,3 +125,103 @@ def test_hook_path_peak_memory_below_gradient_accumulation():
     assert peak_accum >= grad_bytes
     assert peak_adama < 0.15 * grad_bytes
     opt.remove_hooks()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_hooks_adamw_with_scaled_loss_match_oracle(fused):
+    """AdamW with a loss scaled by 1024 (as float16 training does): one mini-batch against the oracle's
+    scaled fold and decoupled-decay update, fed with the gradients autograd produced."""
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import AdamAccumulation, leaf_layers
+
+    torch.backends.cuda.matmul.allow_tf32 = False
+    N, lr, b1, b2, eps, wd, S = 3, 1e-3, 0.9, 0.999, 1e-8, 0.1, 1024.0
+    ref_model = _model(torch)
+    model = copy.deepcopy(ref_model)
+    data = _batches(torch, N, 1)[0]
+    loss_fn = torch.nn.MSELoss()
+    layers = leaf_layers(model)
+    opt = AdamAccumulation(layers, lr=lr, betas=(b1, b2), eps=eps, N=N, fused_edges=fused, weight_decay=wd,
+                           grad_scale=1.0 / S)
+    params = [p for ps in layers for p in ps]
+    ref_params = list(ref_model.parameters())
+    theta = [p.detach().cpu().numpy().ravel().astype(np.float64) for p in params]
+    theta0 = [x.copy() for x in theta]
+    m = [np.zeros_like(x) for x in theta]
+    v = [np.zeros_like(x) for x in theta]
+    opt.begin_mini_batch()
+    for (x, y) in data:
+        ref_model.zero_grad(set_to_none=True)
+        (loss_fn(ref_model(x), y) * S).backward()
+        for i, rp in enumerate(ref_params):
+            oracle.fold_scaled(m[i], v[i], rp.grad.detach().cpu().numpy().ravel(), N, b1, b2, 1.0 / S)
+        (loss_fn(model(x), y) * S).backward()
+        opt.micro_batch_done()
+        assert all(p.grad is None for p in params)
+    opt.step()
+    torch.cuda.synchronize()
+    for i, p in enumerate(params):
+        oracle.apply_adamw(theta[i], m[i], v[i], lr, eps, b1, b2, 1, wd)
+        name = f"adamw hooks fused={fused} param {i}"
+        check_close(name, "m", opt.m[p].cpu().numpy().ravel(), m[i])
+        check_close(name, "v", opt.v[p].cpu().numpy().ravel(), v[i])
+        check_close(name, "theta", p.detach().cpu().numpy().ravel(), theta[i], theta0[i].astype(np.float32), theta0[i])
+    opt.remove_hooks()
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_hooks_momentum_sgd_match_oracle_and_library(fused):
+    """Momentum SGD through the hooks: against the oracle (same micro-batch gradients) and against
+    torch.optim.SGD stepping a twin model on the mean loss."""
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import MomentumAccumulation, leaf_layers
+
+    torch.backends.cuda.matmul.allow_tf32 = False
+    N, lr, mu, steps = 4, 0.05, 0.9, 2
+    twin = _model(torch)
+    model = copy.deepcopy(twin)
+    ref_model = copy.deepcopy(twin)
+    data = _batches(torch, N, steps)
+    loss_fn = torch.nn.MSELoss()
+    layers = leaf_layers(model)
+    opt = MomentumAccumulation(layers, lr=lr, momentum=mu, N=N, fused_edges=fused)
+    lib = torch.optim.SGD(twin.parameters(), lr=lr, momentum=mu)
+    params = [p for ps in layers for p in ps]
+    ref_params = list(ref_model.parameters())
+    theta = [p.detach().cpu().numpy().ravel().astype(np.float64) for p in params]
+    b = [np.zeros_like(x) for x in theta]
+    for step in range(steps):
+        with torch.no_grad():
+            for rp, p in zip(ref_params, params):
+                rp.copy_(p)
+        for i, p in enumerate(params):
+            theta[i][:] = p.detach().cpu().numpy().ravel()
+        prev = [x.copy() for x in theta]
+        opt.begin_mini_batch()
+        lib.zero_grad(set_to_none=True)
+        for i in range(len(b)):
+            oracle.sgdm_begin_step(b[i], mu)
+        for (x, y) in data[step]:
+            ref_model.zero_grad(set_to_none=True)
+            loss_fn(ref_model(x), y).backward()
+            for i, rp in enumerate(ref_params):
+                oracle.sgdm_fold(b[i], rp.grad.detach().cpu().numpy().ravel(), N)
+            loss_fn(model(x), y).backward()
+            opt.micro_batch_done()
+            (loss_fn(twin(x), y) / N).backward()          # the library accumulates the mean gradient
+            assert all(p.grad is None for p in params)
+        opt.step()
+        lib.step()
+        torch.cuda.synchronize()
+        for i, p in enumerate(params):
+            oracle.sgdm_apply(theta[i], b[i], lr, 0.0)
+            name = f"sgdm hooks fused={fused} step {step + 1} param {i}"
+            check_close(name, "m", opt.b[p].cpu().numpy().ravel(), b[i])
+            check_close(name, "theta", p.detach().cpu().numpy().ravel(), theta[i], prev[i].astype(np.float32), prev[i])
+            b[i][:] = opt.b[p].cpu().numpy().ravel()      # keep the oracle on the GPU trajectory
+    # the library's trajectory (float32 autograd on its own parameters) stays within float32 noise of ours
+    for p, q in zip(params, twin.parameters()):
+        assert float((p.detach() - q.detach()).abs().max()) <= 1e-5 * max(1.0, float(q.detach().abs().max()))
+    opt.remove_hooks()
