@@ -96,6 +96,62 @@ def cpu_baseline(w, budget_s: float = 15.0, optimizer: str = "adama") -> dict:
                       f"each (decay + {w.N} folds + update) in {spent:.1f} s, single thread, fp64"}
 
 
+def cpu_baseline_all_cores(w, budget_s: float = 8.0, optimizer: str = "adama") -> dict:
+    """The same oracle loops, unchanged, called from one thread per host core on disjoint contiguous
+    slices of each tensor (the method is elementwise, so slices are independent units)."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    import numpy as np
+
+    import oracle
+    import synth
+
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    gd = None if w.gdtype == "f32" else w.gdtype
+    wd = WEIGHT_DECAY[optimizer]
+
+    def work(theta, m, v, grads):
+        if optimizer == "sgdm":
+            oracle.sgdm_begin_step(m, MOMENTUM)
+            for i in range(w.N):
+                oracle.sgdm_fold(m, grads[i % len(grads)], w.N, 1.0, gdtype=gd)
+            oracle.sgdm_apply(theta, m, w.lr, wd)
+        else:
+            oracle.begin_step(m, v, w.beta1, w.beta2)
+            for i in range(w.N):
+                oracle.fold(m, v, grads[i % len(grads)], w.N, w.beta1, w.beta2, gdtype=gd)
+            if optimizer == "adamw":
+                oracle.apply_adamw(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1, wd)
+            else:
+                oracle.apply(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1)
+
+    spent, params, tensors_done = 0.0, 0, 0
+    big = sorted((t for t in w.tensors if t.n >= 1_000_000), key=lambda t: t.n) or list(w.tensors)
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        for t in big:
+            if spent >= budget_s:
+                break
+            n = t.n
+            theta = synth.fill_host(w.theta_spec(t.index), "f32", n).astype(np.float64)
+            m, v = np.zeros(n), np.zeros(n)
+            grads = [synth.fill_host(w.grad_spec(1, i, t.index), w.gdtype, n) for i in range(min(w.N, 2))]
+            cuts = [n * k // cores for k in range(cores + 1)]
+            t0 = time.perf_counter()
+            jobs = [pool.submit(work, theta[a:b], m[a:b], v[a:b], [g[a:b] for g in grads])
+                    for a, b in zip(cuts[:-1], cuts[1:]) if b > a]
+            for j in jobs:
+                j.result()
+            spent += time.perf_counter() - t0
+            params += n
+            tensors_done += 1
+    per_param = per_param_bytes(w, optimizer)
+    return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "params_per_s": round(params / spent, 1),
+            "sample": f"{tensors_done} large tensor(s) of {w.name} ({params} params), one full mini-batch each, every "
+                      f"tensor cut into {cores} contiguous slices run by {cores} threads calling the unchanged "
+                      f"oracle, {spent:.1f} s, fp64"}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -145,12 +201,24 @@ def main() -> int:
     if not big_layers:        # workloads without such layers: time every big-chunk launch
         big_layers = {li for li in range(len(w.layers)) if w.layer_elems(li) >= tune["big_launch_elems"]}
     fold_events = []
+    class_events = {"decay": [], "fold": [], "update": []}     # (start, end) pairs per kernel class
+
+    def mark():
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(hb.stream)
+        return e
 
     def one_step(timed: bool) -> None:
         """timed: bracket every run of consecutive dominant-kernel launches with one HIP event pair
-        recorded on the launch stream (a pair per launch would add its own overhead to each)."""
+        recorded on the launch stream (a pair per launch would add its own overhead to each), and the
+        decay, each micro-batch's sweep of folds, and the update with one pair each."""
+        t_a = mark() if timed else None
         hb.begin_step(w.beta1, w.beta2)
+        t_b = mark() if timed else None
+        if timed:
+            class_events["decay"].append((t_a, t_b))
         for _ in range(w.N):
+            t_s = mark() if timed else None
             run_start, run_elems, run_launches = None, 0, 0
             for li in w.backward_layers():
                 big = li in big_layers
@@ -170,7 +238,12 @@ def main() -> int:
                 end = torch.cuda.Event(enable_timing=True)
                 end.record(hb.stream)
                 fold_events.append((run_start, end, run_elems, run_launches))
+            if timed:
+                class_events["fold"].append((t_s, mark()))
+        t_c = mark() if timed else None
         hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+        if timed:
+            class_events["update"].append((t_c, mark()))
 
     if args.calibration_copy:
         src = torch.zeros(1 << 30, dtype=torch.uint8, device="cuda:0")
@@ -184,13 +257,17 @@ def main() -> int:
         one_step(False)
     hb.synchronize()
     torch.cuda.synchronize()
+    step_marks = [mark()]
     t0 = time.perf_counter()
     for _ in range(args.steps):
         one_step(False)
+        step_marks.append(mark())          # recorded on the stream, not waited for
     hb.synchronize()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
+    per_step = sorted(a.elapsed_time(b) for a, b in zip(step_marks[:-1], step_marks[1:]))
+    median_ms = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
 
     # ---- the same mini-batch with fused edges (decay inside micro-batch 0's folds, update inside the last) ----
     def one_step_fused() -> None:
@@ -249,6 +326,17 @@ def main() -> int:
     launches = sum(k for _, _, _, k in fold_events)
     achieved = fold_bytes / (fold_ms * 1e-3) / 1e9 if fold_ms > 0 else 0.0
 
+    sb = state_bytes(opt)
+    class_bytes = {"decay": sb * w.P, "fold": (sb + w.grad_bytes) * w.P, "update": (8 + sb // 2) * w.P}
+    kernel_classes = {}
+    for name, pairs in class_events.items():
+        ms = sum(a.elapsed_time(b) for a, b in pairs) / max(len(pairs), 1)
+        if ms > 0:
+            kernel_classes[name] = {"ms": round(ms, 4), "GB/s": round(class_bytes[name] / (ms * 1e-3) / 1e9, 1),
+                                    "params_per_s": round(w.P / (ms * 1e-3), 1)}
+    if "fold" in kernel_classes:
+        kernel_classes["fold"]["us_per_launch"] = round(kernel_classes["fold"]["ms"] * 1e3 / len(w.layers), 2)
+        kernel_classes["fold"]["note"] = "one micro-batch's sweep: one launch per layer"
     step_bytes = algorithmic_bytes_per_step(w, opt)
     value = step_bytes / (ms_per_step * 1e-3) / 1e9
     metric = "AdamA fold+apply effective HBM GB/s (algorithmic bytes of decay + N folds + update per second)"
@@ -264,6 +352,7 @@ def main() -> int:
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3),
+        "ms_per_step_median": round(median_ms, 3),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -281,6 +370,7 @@ def main() -> int:
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},
+        "kernel_classes": kernel_classes,
         "fused_edges": fused,
         "fold_sweep": graph_sweep,
         "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
@@ -293,6 +383,7 @@ def main() -> int:
             out["roofline"]["traffic"] = json.load(fh).get("bytes_per_launch")
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget, opt)
+        out["cpu_baseline_all_cores"] = cpu_baseline_all_cores(w, args.cpu_budget / 2, opt)
     print(json.dumps(out), flush=True)
     return 0
 
