@@ -77,13 +77,19 @@ class WorkloadRun:
     """One workload on the GPU (harness) and in the oracle (on all elements or on sampled slices)."""
 
     def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0",
-                 fused: bool = False):
+                 fused: bool = False, optimizer: str = "adam", momentum: float = 0.9, weight_decay: float = 0.0,
+                 grad_scale: float = 1.0):
         from paper_2305_19982_amd.harness import SimulatedBackward
 
         self.w = w
         self.sampled = sampled
         self.fused = fused      # decay inside micro-batch 0's folds, update inside micro-batch N-1's
-        self.hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, device=device, pack=pack)
+        # variants: "sgdm" keeps its momentum buffer where Adam keeps m (no v); weight decay and the
+        # gradient scale go through the *_opt entry points and the oracle's variant functions
+        self.optimizer, self.momentum, self.weight_decay, self.grad_scale = optimizer, momentum, weight_decay, grad_scale
+        self.hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, device=device, pack=pack,
+                                    optimizer=optimizer, momentum=momentum, weight_decay=weight_decay,
+                                    grad_scale=grad_scale)
         rng = np.random.default_rng(1234)
         self.slices = [slices_of(t.n, rng) if sampled else [(0, t.n)] for t in w.tensors]
         # theta0: the device writes it, the host regenerates the same bits for the oracle
@@ -120,7 +126,12 @@ class WorkloadRun:
             spec = w.grad_spec(step, micro, ti)
             for (r, a, b) in self.rows[ti]:
                 g = synth.fill_host(spec, w.gdtype, b - a, first=a)
-                self.ref.fold(r, g, w.N, w.beta1, w.beta2, gdtype=gd)
+                if self.optimizer == "sgdm":
+                    oracle.sgdm_fold(self.ref.m[r], g, w.N, self.grad_scale, gdtype=gd)
+                elif self.grad_scale != 1.0:
+                    oracle.fold_scaled(self.ref.m[r], self.ref.v[r], g, w.N, w.beta1, w.beta2, self.grad_scale, gdtype=gd)
+                else:
+                    self.ref.fold(r, g, w.N, w.beta1, w.beta2, gdtype=gd)
 
     def run_step(self, step: int, check_grad_bits: bool = False) -> dict:
         w = self.w
@@ -129,7 +140,7 @@ class WorkloadRun:
             self.hb.begin_step_fused()
         else:
             self.hb.begin_step(w.beta1, w.beta2)
-        self.ref.begin_step(w.beta1, w.beta2)
+        self.oracle_begin_step()
         for i in range(w.N):
             for li in w.backward_layers():
                 self.produce(step, i, li)
@@ -144,9 +155,28 @@ class WorkloadRun:
                 self.oracle_fold_layer(step, i, li)
         if not self.fused:
             self.hb.apply(w.lr, w.eps, w.beta1, w.beta2)
-        self.ref.apply(w.lr, w.eps, w.beta1, w.beta2)
+        self.oracle_apply()
         assert self.hb.t == self.ref.t == step
         return self.compare()
+
+    def oracle_begin_step(self) -> None:
+        w = self.w
+        if self.optimizer == "sgdm":
+            self.ref.t += 1
+            for b in self.ref.m:
+                oracle.sgdm_begin_step(b, self.momentum)
+        else:
+            self.ref.begin_step(w.beta1, w.beta2)
+
+    def oracle_apply(self) -> None:
+        w = self.w
+        for th, m, v in zip(self.ref.theta, self.ref.m, self.ref.v):
+            if self.optimizer == "sgdm":
+                oracle.sgdm_apply(th, m, w.lr, self.weight_decay)
+            elif self.weight_decay != 0.0:
+                oracle.apply_adamw(th, m, v, w.lr, w.eps, w.beta1, w.beta2, self.ref.t, self.weight_decay)
+            else:
+                oracle.apply(th, m, v, w.lr, w.eps, w.beta1, w.beta2, self.ref.t)
 
     def assert_grad_bits(self, step: int, micro: int, li: int) -> None:
         """What the device wrote into the gradient buffer is what the host regenerates for the oracle."""
@@ -168,8 +198,10 @@ class WorkloadRun:
         for r, (ti, a, b) in enumerate(self.key):
             name = f"{self.w.name}:{self.w.tensors[ti].name}[{a}:{b}]"
             th = self.download("theta", r)
-            for kind, gpu, ref in (("m", self.download("m", r), self.ref.m[r]),
-                                   ("v", self.download("v", r), self.ref.v[r])):
+            moments = [("m", self.download("m", r), self.ref.m[r])]
+            if self.optimizer != "sgdm":
+                moments.append(("v", self.download("v", r), self.ref.v[r]))
+            for kind, gpu, ref in moments:
                 for k, val in check_close(name, kind, gpu, ref).items():
                     worst[f"{kind}.{k}"] = max(worst.get(f"{kind}.{k}", 0.0), val)
             prev_ref = getattr(self, "_prev_ref_theta", None)

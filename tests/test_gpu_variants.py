@@ -5,7 +5,8 @@ import pytest
 
 import oracle
 import synth
-from parity import check_close
+from parity import WorkloadRun, check_close
+from synth import configs
 
 pytestmark = pytest.mark.gpu
 
@@ -296,3 +297,42 @@ def test_sgdm_matches_library_sgd_on_mean_gradient(torch_cuda):
         opt.step()
     check_close("library SGD", "m", p.host("b"), opt.state[q]["momentum_buffer"].numpy())
     check_close("library SGD", "theta", p.host("t"), q.detach().numpy())
+
+
+# ---------------------------------------------------------------------------
+# the variants on the benchmark workloads (harness, one reusable gradient buffer), reduced and full size
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["c1", "c3", "c4"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_reduced_workload_momentum_sgd(torch_cuda, name, fused):
+    w = configs.reduced(name)
+    run = WorkloadRun(w, pack="tight", fused=fused, optimizer="sgdm", momentum=0.9, weight_decay=0.01)
+    for step in range(1, w.steps + 1):
+        stats = run.run_step(step)
+        print(f"{w.name} [sgdm fused={fused}] step {step}: {stats}", flush=True)
+
+
+@pytest.mark.parametrize("name", ["c1", "c3", "c4"])
+@pytest.mark.parametrize("fused", [False, True])
+def test_reduced_workload_adamw_scaled(torch_cuda, name, fused):
+    w = configs.reduced(name)
+    run = WorkloadRun(w, pack="aligned", fused=fused, weight_decay=0.01, grad_scale=1.0 / 64.0)
+    for step in range(1, w.steps + 1):
+        stats = run.run_step(step)
+        print(f"{w.name} [adamw scaled fused={fused}] step {step}: {stats}", flush=True)
+
+
+@pytest.mark.parametrize("optimizer", ["sgdm", "adamw"])
+def test_full_size_c3_variants_sampled(torch_cuda, optimizer):
+    """The GPT-2-1.5B-shaped workload at full size through the variant entry points (fused edges, as
+    bench.py --optimizer runs them), compared on sampled slices of every tensor."""
+    w = configs.FULL["c3"]()
+    kw = dict(optimizer="sgdm", momentum=0.9) if optimizer == "sgdm" else dict(weight_decay=0.01)
+    run = WorkloadRun(w, pack="aligned", sampled=True, fused=True, **kw)
+    stats = run.run_step(1)
+    print(f"{w.name} [full size, {optimizer}] step 1: {stats}", flush=True)
+    del run
+    import gc
+
+    gc.collect()
+    torch_cuda.cuda.empty_cache()
