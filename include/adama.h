@@ -32,6 +32,10 @@
  *  - Length 0 / count 0 is a successful no-op.  Errors are reported by the return
  *    value, with a message available from adama_last_error(); nothing aborts.
  *    Argument errors are detected before any device work is queued.
+ *  - The library keeps no state between calls (the tensor table of a launch travels in the kernel
+ *    arguments), so calls may be made from several host threads at once, each on its own stream, may be
+ *    recorded into a HIP graph as they are, and work on whichever device is current in the calling
+ *    thread; the pointers and the stream must belong to that device.
  */
 #ifndef ADAMA_H
 #define ADAMA_H

@@ -60,3 +60,64 @@ def test_c5_decoder_10b_full_size():
         pytest.skip(f"needs ~155 GB of free HBM, {free >> 30} GB available")
     peak, whole = _run_full("c5")
     assert peak < whole / 40          # one block (629 MB) vs 25.5 GB
+
+
+def test_single_tensor_longer_than_2_32_elements():
+    """One tensor of 2^32 + 4099 elements (60 GB of theta, m, v and bf16 gradients) through the fused
+    sequence fold_first, fold, fold_last_apply: element indices and byte offsets beyond 32 bits.
+    Compared with the oracle on slices at the start, across the 2^32 boundary, at random places and
+    at the ragged end."""
+    import numpy as np
+    import torch
+
+    import oracle
+    import synth
+    from parity import check_close
+    from paper_2305_19982_amd import binding
+
+    n = (1 << 32) + 4099
+    free, _ = torch.cuda.mem_get_info()
+    if free < 70 * (1 << 30):
+        pytest.skip(f"needs ~61 GB of free HBM, {free >> 30} GB available")
+    t0 = time.time()
+    theta = torch.empty(n, dtype=torch.float32, device="cuda:0")
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    g = torch.empty(n, dtype=torch.bfloat16, device="cuda:0")
+    th_spec = synth.Spec(key=synth.stream_key(71, 0), sigma=0.02)
+    synth.fill_device(theta.data_ptr(), th_spec, "f32", n, 0)
+    rng = np.random.default_rng(5)
+    starts = [0, (1 << 32) - 2048, n - 4099] + [int(x) for x in rng.integers(4096, n - 8192, 5)]
+    slices = [(a, min(a + 4099, n)) for a in starts]
+    ref = oracle.OracleState([synth.fill_host(th_spec, "f32", b - a, first=a) for a, b in slices])
+    th0 = [x.copy() for x in ref.theta]
+    N, b1, b2, lr, eps = 3, 0.9, 0.999, 1e-3, 1e-8
+    ref.begin_step(b1, b2)
+    for i in range(N):
+        spec = synth.Spec(key=synth.stream_key(71, 1 + i), sigma=1e-2, p_zero=0.01, p_outlier=0.001)
+        synth.fill_device(g.data_ptr(), spec, "bf16", n, 0)
+        if i == 0:
+            binding.adama_fold_first(m, v, g, "bf16", n, N, b1, b2)
+        elif i == N - 1:
+            binding.adama_fold_last_apply(theta, m, v, g, "bf16", n, N, lr, eps, b1, b2, 1)
+        else:
+            binding.adama_fold(m, v, g, "bf16", n, N, b1, b2)
+        for r, (a, b) in enumerate(slices):
+            ref.fold(r, synth.fill_host(spec, "bf16", b - a, first=a), N, b1, b2, gdtype="bf16")
+    ref.apply(lr, eps, b1, b2)
+    torch.cuda.synchronize()
+    print(f"  2^32+4099 elements: three passes queued and finished after {time.time() - t0:.1f} s", flush=True)
+    for r, (a, b) in enumerate(slices):
+        name = f"long tensor [{a}:{b}]"
+        check_close(name, "m", m[a:b].cpu().numpy(), ref.m[r])
+        check_close(name, "v", v[a:b].cpu().numpy(), ref.v[r])
+        check_close(name, "theta", theta[a:b].cpu().numpy(), ref.theta[r], th0[r].astype(np.float32), th0[r])
+    # every element was reached: v is positive wherever a gradient was non-zero, which is ~99 % of all
+    # elements; count in pieces to keep temporaries small
+    touched = 0
+    for a in range(0, n, 1 << 28):
+        touched += int((v[a:a + (1 << 28)] > 0).sum())
+    assert touched > 0.95 * n, f"only {touched} of {n} second moments are non-zero"
+    del theta, m, v, g
+    gc.collect()
+    torch.cuda.empty_cache()
