@@ -56,7 +56,9 @@ typedef enum {
     ADAMA_ERR_HIP = 4                 /* a HIP runtime call failed; text in adama_last_error() */
 } adama_status;
 
-typedef enum { ADAMA_F32 = 0, ADAMA_BF16 = 1, ADAMA_F16 = 2 } adama_dtype;
+/* Gradient storage formats.  The last member only widens the enum to the full int range, so that a
+ * value outside the list reaches the library's check (ADAMA_ERR_UNSUPPORTED_DTYPE) as a defined value. */
+typedef enum { ADAMA_F32 = 0, ADAMA_BF16 = 1, ADAMA_F16 = 2, ADAMA_DTYPE_INT_RANGE = 0x7fffffff } adama_dtype;
 
 /* Longest tensor accepted by any call (elements). */
 #define ADAMA_MAX_ELEMS (1ull << 40)

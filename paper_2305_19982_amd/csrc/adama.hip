@@ -58,13 +58,15 @@ constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
 constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long use kUBigOf[op]
 constexpr uint64_t kHugeLaunchElems = 3u << 25;  // 100.7 M elements: launches at least this long use kUHugeOf[op]
 
+// One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
+// a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
+constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
+
+// Groups per thread per chunk for a launch of `op` over `elems` elements.
 int launch_u_for(int op, uint64_t elems)
 {
     return elems >= kHugeLaunchElems ? kUHugeOf[op] : elems >= kBigLaunchElems ? kUBigOf[op] : kUSmall;
 }
-// One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
-// a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
-constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 
 uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF32 ? 4u : 2u; }
 
