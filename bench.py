@@ -356,7 +356,7 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if w.gdtype == "f32" else f"f32 state, {w.gdtype} gradients",
+        "dtype": "f32",                     # the arithmetic type; gradient storage is config.grad_dtype
         "data": "synthetic",
         "config": {"workload": w.name, "params": w.P, "tensors": len(w.tensors), "layers": len(w.layers),
                    "optimizer": opt, "micro_batches": w.N, "grad_dtype": w.gdtype, "bytes_per_step": step_bytes,
