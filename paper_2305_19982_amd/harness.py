@@ -50,7 +50,7 @@ class SimulatedBackward:
     def __init__(self, tensor_sizes: Sequence[int], layers: Sequence[Sequence[int]], gdtype: str,
                  device: str = "cuda:0", stream: torch.cuda.Stream | None = None, pack: str = "aligned",
                  grad_buffer: str = "layer", optimizer: str = "adam", momentum: float = 0.9,
-                 weight_decay: float = 0.0, grad_scale: float = 1.0):
+                 weight_decay: float = 0.0, grad_scale: float = 1.0, arena_stagger_bytes: int | None = None):
         if gdtype not in _GRAD_BYTES:
             raise ValueError(gdtype)
         if optimizer not in ("adam", "sgdm"):
@@ -75,10 +75,24 @@ class SimulatedBackward:
             off = _round_up(off + n, align_elems)
         self.arena_elems = max(off, 1)
         with torch.cuda.stream(self.stream):
-            self.theta = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-            self.m = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-            self.v = (torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-                      if optimizer == "adam" else None)
+            if arena_stagger_bytes is None:
+                self.theta = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+                self.m = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+                self.v = (torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+                          if optimizer == "adam" else None)
+            else:
+                # one slab; arena k starts k * stagger bytes past a 2 MiB boundary of the slab, so the
+                # low address bits of m[i], v[i] and theta[i] differ by a chosen amount
+                if arena_stagger_bytes % 256 or arena_stagger_bytes < 0:
+                    raise ValueError("arena_stagger_bytes must be a non-negative multiple of 256")
+                two_mib = 1 << 21
+                pitch = _round_up(self.arena_elems * 4 + 2 * arena_stagger_bytes, two_mib)
+                narena = 3 if optimizer == "adam" else 2
+                self._slab = torch.zeros(narena * pitch + two_mib, dtype=torch.uint8, device=self.device)
+                base = (-self._slab.data_ptr()) % two_mib
+                views = [self._slab[base + k * (pitch + arena_stagger_bytes):][: self.arena_elems * 4].view(torch.float32)
+                         for k in range(narena)]
+                self.m, self.v, self.theta = (views[0], views[1], views[2]) if narena == 3 else (views[0], None, views[1])
         # ---- the one gradient buffer: layer-local offsets, reused by every layer ----
         self.grad_offset = [0] * len(self.sizes)             # element offset inside the buffer
         largest = 0

@@ -548,3 +548,30 @@ def test_concurrent_host_threads_on_their_own_streams(torch_cuda):
         oracle.fold(rm, rv, synth.fill_host(synth.Spec(key=1000 + r, sigma=1e-2), "bf16", n), N, B1, B2, gdtype="bf16")
     check_close("threads", "m", results[0][0], rm)
     check_close("threads", "v", results[0][1], rv)
+
+
+def test_arena_placement_does_not_change_results(torch_cuda):
+    """The harness can place theta, m, v in one slab with the arenas staggered against each other (a
+    knob for measuring how relative placement affects bandwidth); results are bit-identical."""
+    torch = torch_cuda
+    from paper_2305_19982_amd.harness import SimulatedBackward
+
+    w = configs.reduced("c3")
+    outs = []
+    for stagger in (None, 0, 4096):
+        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, pack="tight", arena_stagger_bytes=stagger)
+        for t in w.tensors:
+            synth.fill_device(hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, hb.stream_handle)
+
+        def produce(i, li, hb=hb):
+            for ti in w.layers[li]:
+                synth.fill_device(hb.grad_ptr(ti), w.grad_spec(1, i, ti), w.gdtype, w.tensors[ti].n, hb.stream_handle)
+
+        hb.mini_batch(produce, w.N, w.lr, w.eps, w.beta1, w.beta2)
+        hb.synchronize()
+        outs.append([torch.cat([hb.tensor_view(k, t.index) for t in w.tensors]).clone() for k in ("theta", "m", "v")])
+        if stagger is not None:
+            assert (hb.v.data_ptr() - hb.m.data_ptr()) % (1 << 21) == stagger
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
