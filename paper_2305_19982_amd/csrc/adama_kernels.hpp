@@ -21,7 +21,7 @@
 // data (there is no reuse), only wide coalesced accesses and enough of them in
 // flight.  A workgroup of 256 threads handles one chunk of 1024*U elements;
 // inside an interior chunk each thread issues all of its U 16-byte loads per
-// array before the first use, so a wavefront has 2U..4U independent 1-KiB
+// array before the first use, so a wavefront has U..4U independent 1-KiB
 // requests outstanding.  The table of tensors of the launch arrives in the
 // kernel argument block, together with the per-tensor chunk prefix that maps a
 // chunk number to its tensor; both are read through the scalar cache.

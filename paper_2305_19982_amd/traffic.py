@@ -32,6 +32,31 @@ def _per_kernel(path: str, counter: str):
     return rows
 
 
+def summarise(fetch_csv: str, write_csv: str, kernel_regex: str, workload: str) -> dict:
+    """Bytes per launch of the kernels matching `kernel_regex`, from one FETCH_SIZE and one WRITE_SIZE
+    run, each scaled by the same counter's reading for the one calibration copy in that run."""
+    out = {"workload": workload, "unit": "bytes"}
+    per_launch = {}
+    for name, path, counter in (("fetch", fetch_csv, "FETCH_SIZE"), ("write", write_csv, "WRITE_SIZE")):
+        rows = _per_kernel(path, counter)
+        copy = [v for k, vals in rows.items() if "synth_copy_kernel" in k for _, v in vals]
+        if len(copy) != 1:
+            raise SystemExit(f"{path}: expected exactly one synth_copy_kernel dispatch, found {len(copy)}")
+        if copy[0] <= 0:
+            raise SystemExit(f"{path}: the calibration copy read {copy[0]} KiB")
+        scale = COPY_BYTES / (copy[0] * 1024.0)
+        dom = [v for k, vals in rows.items() if re.search(kernel_regex, k) for _, v in vals]
+        if not dom:
+            raise SystemExit(f"{path}: no dispatch matches {kernel_regex!r}")
+        per_launch[name] = sum(dom) / len(dom) * 1024.0 * scale
+        out[f"{name}_scale"] = round(scale, 4)
+        out[f"{name}_copy_kib"] = copy[0]
+        out[f"{name}_bytes_per_launch"] = round(per_launch[name])
+        out["launches"] = len(dom)
+    out["bytes_per_launch"] = round(per_launch["fetch"] + per_launch["write"])
+    return out
+
+
 def main() -> None:
     ap = argparse.ArgumentParser()
     ap.add_argument("--fetch", required=True)
@@ -47,23 +72,7 @@ def main() -> None:
 
         u = binding.adama_launch_chunk("fold", args.launch_elems) // 1024
         args.kernel = rf"multi_tensor_kernel<1, \d, {u}, \d+, false>"
-    out = {"workload": args.workload, "unit": "bytes"}
-    per_launch = {}
-    for name, path, counter in (("fetch", args.fetch, "FETCH_SIZE"), ("write", args.write, "WRITE_SIZE")):
-        rows = _per_kernel(path, counter)
-        copy = [v for k, vals in rows.items() if "synth_copy_kernel" in k for _, v in vals]
-        if len(copy) != 1:
-            raise SystemExit(f"{path}: expected exactly one synth_copy_kernel dispatch, found {len(copy)}")
-        scale = COPY_BYTES / (copy[0] * 1024.0)
-        dom = [v for k, vals in rows.items() if re.search(args.kernel, k) for _, v in vals]
-        if not dom:
-            raise SystemExit(f"{path}: no dispatch matches {args.kernel!r}")
-        per_launch[name] = sum(dom) / len(dom) * 1024.0 * scale
-        out[f"{name}_scale"] = round(scale, 4)
-        out[f"{name}_copy_kib"] = copy[0]
-        out[f"{name}_bytes_per_launch"] = round(per_launch[name])
-        out["launches"] = len(dom)
-    out["bytes_per_launch"] = round(per_launch["fetch"] + per_launch["write"])
+    out = summarise(args.fetch, args.write, args.kernel, args.workload)
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     dst = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")
     with open(dst, "w") as fh:
