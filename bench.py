@@ -343,7 +343,7 @@ def main() -> int:
     if opt != "adama":
         metric = f"{opt} variant: " + metric
     op_label = "sgd_fold" if opt == "sgdm" else "fold"
-    dom_chunk = binding.adama_launch_chunk(op_label, max((w.layer_elems(li) for li in big_layers), default=0))
+    dom = binding.adama_tuning(op_label, max((w.layer_elems(li) for li in big_layers), default=0))
     out = {
         "metric": metric,
         "value": round(value, 1),
@@ -366,7 +366,7 @@ def main() -> int:
         "frac_hbm_peak": round(value / HBM_PEAK_GBS, 4),
         "roofline": {"bound": "hbm", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
-                     "kernel": f"multi_tensor_kernel<{op_label},{w.gdtype},U={dom_chunk // 1024},policy={tune['policy_bits']},multi-tensor>",
+                     "kernel": f"multi_tensor_kernel<{op_label},{w.gdtype},block={dom['block']},U={dom['groups_per_thread']},policy={dom['policy_bits']},multi-tensor>",
                      "launches_timed": launches,
                      "avg_launch_ms": round(fold_ms / launches, 4) if launches else None,
                      "bytes_per_launch": round(fold_bytes / launches) if launches else None},

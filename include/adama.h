@@ -243,11 +243,15 @@ const char *adama_last_error(void);
 #define ADAMA_MAX_TENSORS_PER_LAUNCH 80
 int adama_max_tensors_per_launch(void);
 
-/* Host-only: the launch policy compiled into the library, for benchmark labels.  A fold launch whose
- * tensors total at least *big_launch_elems elements uses chunks of 1024 * *u_big elements (other ops
- * have their own factor), shorter launches use 1024 * *u_small; *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal
- * state loads, 4 = non-temporal stores.  Any pointer may be NULL. */
-void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits);
+/* Host-only: the launch policy compiled into the library, for benchmark labels and profile filters.
+ * For a launch of op `op` (numbering as in adama_debug_walk) over tensors totalling `launch_elems`
+ * elements: *block = threads per workgroup, *groups_per_thread = 4-element groups each thread moves per
+ * array (one workgroup handles block * 4 * groups elements; both 0 for an unknown op);
+ * *big_launch_elems = the launch length from which the op's large-launch shape is used;
+ * *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal state loads, 4 = non-temporal stores.
+ * Any pointer may be NULL. */
+void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
+                  unsigned long long *big_launch_elems, int *policy_bits);
 
 /* Host-only: the chunk size (elements handled by one workgroup) the library uses for a launch of op
  * `op` (numbering as in adama_debug_walk) over tensors totalling `launch_elems` elements; 0 for an

@@ -115,8 +115,8 @@ def load() -> ctypes.CDLL:
     lib.adama_launch_chunk.restype = i32
     lib.adama_launch_chunk.argtypes = [i32, ctypes.c_ulonglong]
     lib.adama_tuning.restype = None
-    lib.adama_tuning.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_ulonglong),
-                                 ctypes.POINTER(i32)]
+    lib.adama_tuning.argtypes = [i32, ctypes.c_ulonglong, ctypes.POINTER(i32), ctypes.POINTER(i32),
+                                 ctypes.POINTER(ctypes.c_ulonglong), ctypes.POINTER(i32)]
     _lib = lib
     return lib
 
@@ -150,10 +150,13 @@ def adama_launch_chunk(op, launch_elems: int) -> int:
     return int(load().adama_launch_chunk(OPS.get(op, op), int(launch_elems)))
 
 
-def adama_tuning() -> dict:
-    us, ub, pol, big = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_ulonglong(0)
-    load().adama_tuning(ctypes.byref(us), ctypes.byref(ub), ctypes.byref(big), ctypes.byref(pol))
-    return {"u_small": us.value, "u_big": ub.value, "big_launch_elems": big.value, "policy_bits": pol.value}
+def adama_tuning(op="fold", launch_elems: int = 1 << 25) -> dict:
+    """Workgroup shape, large-launch threshold and cache-policy bits for a launch of `op` over `launch_elems` elements."""
+    blk, grp, pol, big = ctypes.c_int(0), ctypes.c_int(0), ctypes.c_int(0), ctypes.c_ulonglong(0)
+    load().adama_tuning(OPS.get(op, op), int(launch_elems), ctypes.byref(blk), ctypes.byref(grp), ctypes.byref(big),
+                        ctypes.byref(pol))
+    return {"block": blk.value, "groups_per_thread": grp.value, "big_launch_elems": big.value,
+            "policy_bits": pol.value}
 
 
 def tensor_list(entries) -> ctypes.Array:

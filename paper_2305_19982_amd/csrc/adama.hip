@@ -32,40 +32,49 @@ adama_status fail(adama_status st, const char *fmt, ...)
     return st;
 }
 
-// ---- tuning constants (measured on MI355X with a sweep over U, grid shape and cache policy) ----
-constexpr int kUSmall = 1;                    // chunk = 1024 elements: many workgroups for small launches
-// Groups per thread per chunk by op (index = Op) for launches of at least kBigLaunchElems elements, and
-// for launches of at least kHugeLaunchElems.  Measured per op on whole transformer blocks (12.6 M .. 315 M
-// elements per launch) and on whole-state lists: the folds, which have the most independent streams, do
-// best with 2 groups (2048-element chunks, 6 16-byte loads in flight per thread) up to about 64 M elements
-// per launch (+1.5 % over 4 groups: twice as many workgroups fill the last partial wave of the grid
-// better) and with 4 groups from about 120 M elements on (+0.5..1.5 %); the first-micro-batch form was
-// repeatably 1..2 % faster with 4 at every size; everything that ends in the update, and the plain
-// decay, do best with 1 (+6..9 % for the update, whose three read streams and long dependent arithmetic
-// leave the fewest registers for loads in flight); the single-moment SGD ops with 2.
-#ifndef ADAMA_U_BIG_TABLE
-#define ADAMA_U_BIG_TABLE {1, 2, 1, 4, 1, 1, 2, 2, 2, 2, 2}
-#endif
-#ifndef ADAMA_U_HUGE_TABLE
-#define ADAMA_U_HUGE_TABLE {1, 4, 1, 4, 1, 1, 2, 2, 2, 2, 2}
-#endif
-constexpr int kUBigOf[kNumOps] = ADAMA_U_BIG_TABLE;
-constexpr int kUHugeOf[kNumOps] = ADAMA_U_HUGE_TABLE;
-constexpr int kUBig = kUBigOf[kFold];
+// ---- launch policy (measured on MI355X: sweeps over workgroup size, groups per thread, grid shape, cache policy) ----
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
-constexpr uint64_t kBigLaunchElems = 1u << 20;   // launches at least this long use kUBigOf[op]
-constexpr uint64_t kHugeLaunchElems = 3u << 25;  // 100.7 M elements: launches at least this long use kUHugeOf[op]
-
 // One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
 // a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
+constexpr uint64_t kBigLaunchElems = 1u << 20;           // "big" launches: at least this many elements
+constexpr uint64_t kHugeLaunchElems = 3u << 25;          // "huge" launches: at least 100.7 M elements
 
-// Groups per thread per chunk for a launch of `op` over `elems` elements.
-int launch_u_for(int op, uint64_t elems)
+// Workgroup shape per op (index = Op) for small, big and huge launches.  Measured per op, as alternating
+// processes on one box, on whole transformer blocks (12.6 M .. 315 M elements per launch) and whole-state
+// lists.  The folds and the decay stream best through many small workgroups (128 threads x 1 group =
+// 512-element chunks: +0.9 % on 30 M-element launches over 256 x 1, +2 % over 256 x 2, +3.5 % over
+// 256 x 4; a CU refills at a finer grain and the grid's tail is shorter), except on launches beyond
+// about 100 M elements, where 256 x 4 is 0.4 % ahead.  Everything that ends in the update does best
+// with 256 x 1 (128 x 1 is 3 % slower there, 256 x 4 is 8 % slower: three read streams and long
+// dependent arithmetic).  The single-moment SGD ops move fewer bytes per element and need two groups
+// per thread to keep enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds, 128 x 2
+// for decay (+5 %) and update (+2 %).  Launches under 2^20 elements are latency-bound and use 256 x 1.
+struct Policy {
+    Shape small, big, huge;
+};
+#ifndef ADAMA_POLICY_TABLE
+#define ADAMA_POLICY_TABLE {                                                         \
+    /* decay             */ {{256, 1}, {128, 1}, {256, 1}},                          \
+    /* fold              */ {{256, 1}, {128, 1}, {256, 4}},                          \
+    /* apply             */ {{256, 1}, {256, 1}, {256, 1}},                          \
+    /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}},                          \
+    /* fold_last_apply   */ {{256, 1}, {256, 1}, {256, 1}},                          \
+    /* rescale_apply     */ {{256, 1}, {256, 1}, {256, 1}},                          \
+    /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}},                          \
+    /* sgd fold          */ {{256, 1}, {256, 2}, {256, 2}},                          \
+    /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}},                          \
+    /* sgd fold_first    */ {{256, 1}, {256, 2}, {256, 2}},                          \
+    /* sgd fold_last_apply */ {{256, 1}, {256, 2}, {256, 2}},                        \
+}
+#endif
+constexpr Policy kPolicy[kNumOps] = ADAMA_POLICY_TABLE;
+
+Shape launch_shape_for(int op, uint64_t elems)
 {
-    return elems >= kHugeLaunchElems ? kUHugeOf[op] : elems >= kBigLaunchElems ? kUBigOf[op] : kUSmall;
+    return elems >= kHugeLaunchElems ? kPolicy[op].huge : elems >= kBigLaunchElems ? kPolicy[op].big : kPolicy[op].small;
 }
 
 uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF32 ? 4u : 2u; }
@@ -73,7 +82,7 @@ uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF3
 // One launch: tensors [first, first+count) of the caller's list with their chunk prefix.
 struct Batch {
     Table<kMaxTensors> tab;
-    int u;                 // groups per thread per chunk
+    Shape shape;           // workgroup size and groups per thread
     uint32_t total;        // chunks
 };
 
@@ -92,8 +101,8 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
             elems += descs[i + k].n;
             ++k;
         }
-        b.u = launch_u_for(op, elems);
-        const uint32_t chunk = kBlock * kGroup * b.u;
+        b.shape = launch_shape_for(op, elems);
+        const uint32_t chunk = chunk_elems(b.shape);
         uint64_t start = 0;
         for (int j = 0; j < k; ++j) {
             b.tab.chunk_start[j] = (uint32_t)start;
@@ -114,21 +123,24 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
     return ADAMA_OK;
 }
 
-template <int OpK, int GT, int U>
+template <int OpK, int GT, int BLOCK, int U>
 void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
+    static_assert(BLOCK % 64 == 0 && BLOCK <= kMaxBlock && U >= 1, "workgroup shape");
     if (b.tab.count == 1)
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, U, kNtPolicy, true>), dim3(b.total), dim3(kBlock), 0, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, true>), dim3(b.total), dim3(BLOCK), 0, stream, b.tab, sc);
     else
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, U, kNtPolicy, false>), dim3(b.total), dim3(kBlock), 0, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, false>), dim3(b.total), dim3(BLOCK), 0, stream, b.tab, sc);
 }
 
+// Picks the instantiation for the batch's shape, which is one of the op's three.
 template <int OpK, int GT>
 void launch_u(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
-    if (b.u == kUSmall) launch_one<OpK, GT, kUSmall>(b, sc, stream);
-    else if (b.u == kUBigOf[OpK]) launch_one<OpK, GT, kUBigOf[OpK]>(b, sc, stream);
-    else launch_one<OpK, GT, kUHugeOf[OpK]>(b, sc, stream);
+    constexpr Policy P = kPolicy[OpK];
+    if (same_shape(b.shape, P.small)) launch_one<OpK, GT, P.small.block, P.small.u>(b, sc, stream);
+    else if (same_shape(b.shape, P.big)) launch_one<OpK, GT, P.big.block, P.big.u>(b, sc, stream);
+    else launch_one<OpK, GT, P.huge.block, P.huge.u>(b, sc, stream);
 }
 
 template <int OpK>
@@ -372,13 +384,15 @@ int adama_max_tensors_per_launch(void) { return kMaxTensors; }
 int adama_launch_chunk(int op, unsigned long long launch_elems)
 {
     if (op < 0 || op >= kNumOps) return 0;
-    return kBlock * kGroup * launch_u_for(op, launch_elems);
+    return (int)chunk_elems(launch_shape_for(op, launch_elems));
 }
 
-void adama_tuning(int *u_small, int *u_big, unsigned long long *big_launch_elems, int *policy_bits)
+void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
+                  unsigned long long *big_launch_elems, int *policy_bits)
 {
-    if (u_small) *u_small = kUSmall;
-    if (u_big) *u_big = kUBig;
+    const Shape s = (op >= 0 && op < kNumOps) ? launch_shape_for(op, launch_elems) : Shape{0, 0};
+    if (block) *block = s.block;
+    if (groups_per_thread) *groups_per_thread = s.u;
     if (big_launch_elems) *big_launch_elems = kBigLaunchElems;
     if (policy_bits) *policy_bits = kNtPolicy;
 }
@@ -620,7 +634,7 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
         for (int j = 0; j < kp; ++j) piece[j] = walk_desc(op, list[i0 + j]);
         adama_status st = for_each_batch(op, piece, kp, [&](const Batch &b, int first) -> adama_status {
             ++nlaunch;
-            const uint32_t chunk = kBlock * kGroup * b.u;
+            const uint32_t chunk = chunk_elems(b.shape);
             const uint32_t cnt = b.tab.count;
             const int base = i0 + first;   // list index of the batch's first tensor
             for (uint32_t c = 0; c < b.total; ++c) {
@@ -631,9 +645,9 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
                 const bool vec = coaligned(d, ns, gb);
                 unsigned char *tch = touched[base + (int)k];
                 const bool interior = chunk_is_interior(vec, pre, d.n, lc, chunk);
-                for (int u = 0; u < b.u; ++u) {
-                    for (uint32_t tid = 0; tid < (uint32_t)kBlock; ++tid) {
-                        const uint64_t coord = lc * chunk + (uint64_t)(u * kBlock + tid) * kGroup;
+                for (int u = 0; u < b.shape.u; ++u) {
+                    for (uint32_t tid = 0; tid < (uint32_t)b.shape.block; ++tid) {
+                        const uint64_t coord = lc * chunk + (uint64_t)(u * b.shape.block + tid) * kGroup;
                         const int kind = interior ? 2 : group_kind(vec, pre, d.n, coord);
                         if (kind == 2) {
                             if (coord < pre) return fail(ADAMA_ERR_INVALID_ARG, "vector access before tensor %d", base + (int)k);

@@ -1,7 +1,7 @@
 // Launch geometry shared by the kernels and by the host-side geometry walk.
 //
 // One launch processes up to kMaxTensors tensors.  Each tensor is cut into
-// chunks of `chunk` elements measured in "aligned coordinates": element e of a
+// chunks of `chunk` elements (see Shape) measured in "aligned coordinates": element e of a
 // tensor sits at coordinate pre + e, where pre (0..3) is the number of float32
 // elements by which the tensor's first state array is past a 16-byte boundary.
 // Coordinates that are multiples of 4 therefore fall on 16-byte boundaries of
@@ -22,7 +22,7 @@
 
 namespace adama {
 
-constexpr int kBlock = 256;       // threads per workgroup: four 64-wide wavefronts
+constexpr int kMaxBlock = 256;    // largest workgroup any launch uses: four 64-wide wavefronts
 constexpr int kGroup = 4;         // elements per 16-byte float32 access
 constexpr int kMaxTensors = 80;   // descriptors per launch (table lives in the kernel argument block)
 
@@ -60,6 +60,14 @@ ADAMA_HD constexpr int op_store_mask(int op)
 {
     return (op == kApply || op == kSgdApply) ? 1 : (1 << op_states(op)) - 1;
 }
+
+// Shape of a launch's workgroups: `block` threads, each moving `u` 4-element groups per array, so one
+// workgroup handles a chunk of block * 4 * u elements.
+struct Shape {
+    int block, u;
+};
+ADAMA_HD constexpr uint32_t chunk_elems(Shape s) { return (uint32_t)(s.block * kGroup * s.u); }
+ADAMA_HD constexpr bool same_shape(Shape a, Shape b) { return a.block == b.block && a.u == b.u; }
 
 // The arrays of one tensor: up to three float32 state arrays and the gradient.
 struct Desc {

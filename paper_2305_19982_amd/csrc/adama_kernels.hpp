@@ -19,7 +19,7 @@
 //
 // so the design goal is HBM bandwidth, not arithmetic: no MFMA, no LDS tiling of
 // data (there is no reuse), only wide coalesced accesses and enough of them in
-// flight.  A workgroup of 256 threads handles one chunk of 1024*U elements;
+// flight.  A workgroup of BLOCK threads handles one chunk of BLOCK*4*U elements;
 // inside an interior chunk each thread issues all of its U 16-byte loads per
 // array before the first use, so a wavefront has U..4U independent 1-KiB
 // requests outstanding.  The table of tensors of the launch arrives in the
@@ -152,7 +152,7 @@ __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars
 }
 
 // ---- one interior chunk: every group is a full aligned group; all loads first ----
-template <int OpK, int GT, int U, int NT>
+template <int OpK, int GT, int BLOCK, int U, int NT>
 __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint32_t tid, const Scalars &sc)
 {
     constexpr bool ntg = (NT & kNtGradLoad) != 0, ntl = (NT & kNtStateLoad) != 0, nts = (NT & kNtStore) != 0;
@@ -172,14 +172,14 @@ __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint3
     // (On small footprints array-major wins by 2 % instead; the order that holds up at scale is kept.)
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = u * kBlock + tid;
+        const uint32_t i = u * BLOCK + tid;
         if constexpr (op_has_grad(OpK)) g[u] = ld<ntg>(Gp + i);
 #pragma unroll
         for (int k = 0; k < NS; ++k) x[k][u] = ld<ntl>(S[k] + i);
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        const uint32_t i = u * kBlock + tid;
+        const uint32_t i = u * BLOCK + tid;
         f32x4 gf = {0.0f, 0.0f, 0.0f, 0.0f};
         if constexpr (op_has_grad(OpK)) gf = G::widen(g[u]);
 #pragma unroll
@@ -243,8 +243,9 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
     }
 }
 
-// OpK: Op.  GT: GradType (ops with a gradient).  U: 16-byte groups per thread per chunk (chunk =
-// 1024*U elements).  NT: cache-policy bits.  SINGLE: the launch holds exactly one tensor.
+// OpK: Op.  GT: GradType (ops with a gradient).  BLOCK: threads per workgroup.  U: 16-byte groups per
+// thread per chunk (chunk = BLOCK*4*U elements).  NT: cache-policy bits.  SINGLE: the launch holds
+// exactly one tensor.
 // Launch contract: gridDim.x == tab.total, one workgroup per chunk.
 //
 // The tensor table stays in the kernel argument block and is read with scalar loads: the chunk number
@@ -253,12 +254,12 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
 // scalar-load round trips (one for a single-tensor launch).  (Staging the table in LDS first was
 // measured and dropped: in a kernel that saturates the vector memory path, the vector loads that
 // would fill LDS queue behind the streaming traffic and delay every workgroup's first data load.)
-template <int OpK, int GT, int U, int NT, bool SINGLE>
-__global__ void __launch_bounds__(kBlock) multi_tensor_kernel(const Table<kMaxTensors> tab, const Scalars sc)
+template <int OpK, int GT, int BLOCK, int U, int NT, bool SINGLE>
+__global__ void __launch_bounds__(BLOCK) multi_tensor_kernel(const Table<kMaxTensors> tab, const Scalars sc)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t c = blockIdx.x;
-    constexpr uint32_t chunk = kBlock * kGroup * U;
+    constexpr uint32_t chunk = BLOCK * kGroup * U;
     constexpr uint32_t g_bytes = !op_has_grad(OpK) ? 0u : GT == kF32 ? 4u : 2u;
     const uint32_t k = SINGLE ? 0u : find_tensor(tab.chunk_start, c);
     const Desc d = tab.t[k];
@@ -266,11 +267,11 @@ __global__ void __launch_bounds__(kBlock) multi_tensor_kernel(const Table<kMaxTe
     const uint32_t pre = misalign_elems(d.s[0]);
     const bool vec = coaligned(d, op_states(OpK), g_bytes);
     if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {
-        interior_chunk<OpK, GT, U, NT>(d, lc * chunk - pre, tid, sc);
+        interior_chunk<OpK, GT, BLOCK, U, NT>(d, lc * chunk - pre, tid, sc);
     } else {
 #pragma unroll 1
         for (int u = 0; u < U; ++u)
-            boundary_group<OpK, GT>(d, vec, pre, lc * chunk + (uint64_t)(u * kBlock + tid) * kGroup, sc);
+            boundary_group<OpK, GT>(d, vec, pre, lc * chunk + (uint64_t)(u * BLOCK + tid) * kGroup, sc);
     }
 }
 

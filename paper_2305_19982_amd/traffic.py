@@ -70,8 +70,8 @@ def main() -> None:
     if args.kernel is None:
         from . import binding
 
-        u = binding.adama_launch_chunk("fold", args.launch_elems) // 1024
-        args.kernel = rf"multi_tensor_kernel<1, \d, {u}, \d+, false>"
+        t = binding.adama_tuning("fold", args.launch_elems)
+        args.kernel = rf"multi_tensor_kernel<1, \d, {t['block']}, {t['groups_per_thread']}, \d+, false>"
     out = summarise(args.fetch, args.write, args.kernel, args.workload)
     os.makedirs(os.path.join(ROOT, "profiles"), exist_ok=True)
     dst = os.path.join(ROOT, "profiles", f"traffic_{args.workload}.json")

@@ -281,11 +281,14 @@ def test_geometry_chunk_size_follows_launch_size(lib):
     sizes = {n: binding.adama_launch_chunk("fold", n) for n in (1, (1 << 20) - 1, 1 << 20, 30_740_800, 3 << 25, 1 << 30)}
     assert sizes[1] == sizes[(1 << 20) - 1] == 1024
     assert sizes[1 << 20] == sizes[30_740_800] and sizes[3 << 25] == sizes[1 << 30]
-    assert 1024 < sizes[1 << 20] <= sizes[3 << 25]
+    assert sizes[1 << 20] <= sizes[3 << 25]
     assert binding.adama_launch_chunk(99, 5) == 0
     for op in range(11):
         for n in (5, 1 << 22, 1 << 28):
-            assert binding.adama_launch_chunk(op, n) in (1024, 2048, 4096)
+            t = binding.adama_tuning(op, n)
+            assert t["block"] in (64, 128, 256) and 1 <= t["groups_per_thread"] <= 8
+            assert binding.adama_launch_chunk(op, n) == t["block"] * 4 * t["groups_per_thread"]
+    assert binding.adama_tuning(99, 5)["block"] == 0
     # one launch past the upper threshold, misaligned start: every element once, in bounds
     n = (3 << 25) + 5
     entries = [(FAKE + (3 << 40) + 12, FAKE + 12, FAKE + (1 << 40) + 12, FAKE + (2 << 40) + 6, n)]

@@ -10,8 +10,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-FOLD = "void adama::multi_tensor_kernel<1, 1, 2, 7, false>(adama::Table<80>, adama::Scalars)"
-OTHER = "void adama::multi_tensor_kernel<2, 0, 1, 7, false>(adama::Table<80>, adama::Scalars)"
+FOLD = "void adama::multi_tensor_kernel<1, 1, 128, 1, 7, false>(adama::Table<80>, adama::Scalars)"
+OTHER = "void adama::multi_tensor_kernel<2, 0, 256, 1, 7, false>(adama::Table<80>, adama::Scalars)"
 COPY = "synth_copy_kernel(float __vector(4)*, float __vector(4) const*, unsigned long)"
 
 
@@ -31,7 +31,7 @@ def test_traffic_summary_scales_by_the_calibration_copy(tmp_path):
     # the fetch counter reads half of the real KiB (as on MI355X), the write counter the real KiB
     _write(f, "FETCH_SIZE", [(COPY, 524288.0), (FOLD, 1000.0), (OTHER, 77.0), (FOLD, 3000.0)])
     _write(w, "WRITE_SIZE", [(COPY, 1048576.0), (FOLD, 1600.0), (FOLD, 4800.0), (OTHER, 5.0)])
-    out = traffic.summarise(f, w, r"multi_tensor_kernel<1, \d, 2, \d+, false>", "unit_test")
+    out = traffic.summarise(f, w, r"multi_tensor_kernel<1, \d, 128, 1, \d+, false>", "unit_test")
     assert out["fetch_scale"] == 2.0 and out["write_scale"] == 1.0 and out["launches"] == 2
     assert out["fetch_bytes_per_launch"] == 2000 * 1024 * 2
     assert out["write_bytes_per_launch"] == 3200 * 1024
