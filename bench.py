@@ -165,6 +165,8 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="also time one micro-batch's fold sweep as eager launches and as a HIP graph replay")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--no-torch-ops", action="store_true",
+                    help="skip the context figure for the same fold written as stock PyTorch tensor ops")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (no sharding, no collectives); run with --gpus 1",
@@ -302,6 +304,42 @@ def main() -> int:
             graph_sweep = dict(graph_sweep or {}, **{f"{label}_us_per_launch": round(us, 2)})
         graph_sweep["launches_per_sweep"] = len(w.layers)
 
+    # ---- context: the fold of one micro-batch written as stock PyTorch tensor ops (the style of the
+    # paper's own hook implementation), on the same tensors, same GPU.  Not the product path.
+    torch_ops = None
+    if not args.no_torch_ops and opt != "sgdm" and w.P <= 4_000_000_000:
+        tdt = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}[w.gdtype]
+        c1, c2 = (1.0 - w.beta1) / w.N, (1.0 - w.beta2) / (w.N * w.N)
+        views = []
+        for li in w.backward_layers():
+            ms_, vs_, gs_ = [], [], []
+            for ti in w.layers[li]:
+                n, go = w.tensors[ti].n, hb.grad_offset[ti] * hb.gbytes
+                ms_.append(hb.tensor_view("m", ti))
+                vs_.append(hb.tensor_view("v", ti))
+                gs_.append(hb.grad_buffer[go: go + n * hb.gbytes].view(tdt))
+            views.append((ms_, vs_, gs_))
+
+        def torch_sweep() -> None:
+            for ms_, vs_, gs_ in views:
+                g32 = [g.float() for g in gs_] if tdt != torch.float32 else gs_
+                torch._foreach_add_(ms_, g32, alpha=c1)
+                torch._foreach_addcmul_(vs_, g32, g32, value=c2)
+
+        with torch.cuda.stream(hb.stream):
+            torch_sweep()
+            hb.synchronize()
+            t3 = time.perf_counter()
+            for _ in range(3):
+                torch_sweep()
+            hb.synchronize()
+            tms = (time.perf_counter() - t3) / 3 * 1e3
+        torch_ops = {"fold_sweep_ms": round(tms, 3),
+                     "GB/s": round((state_bytes(opt) + w.grad_bytes) * w.P / (tms * 1e-3) / 1e9, 1),
+                     "note": "one micro-batch's folds as torch._foreach_add_ / _foreach_addcmul_ on the same tensors "
+                             "(float32 copy of 16-bit gradients first); algorithmic bytes / time; context only"}
+        del views
+
     fused = None
     if w.N > 1:
         one_step_fused()
@@ -373,6 +411,7 @@ def main() -> int:
         "kernel_classes": kernel_classes,
         "fused_edges": fused,
         "fold_sweep": graph_sweep,
+        "torch_ops_baseline": torch_ops,
         "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
                         "whole_model_bytes": w.P * w.grad_bytes},
