@@ -51,23 +51,26 @@ def algorithmic_bytes_per_step(w, optimizer: str = "adama") -> int:
 
 
 def cpu_baseline(w, budget_s: float = 15.0, optimizer: str = "adama") -> dict:
-    """The fp64 oracle, as it stands, timed on this host over whole layers of the same workload
-    (one full mini-batch each: decay, N folds, update) until about `budget_s` seconds are used."""
+    """The fp64 oracle, as it stands, timed on this host over the tensors of whole layers of the same
+    workload (one full mini-batch each: decay, N folds, update) until about `budget_s` seconds are
+    used.  Tensors longer than 16 M elements contribute their first 16 M (the method is elementwise, so
+    a prefix is a fair sample)."""
     import numpy as np
 
     import oracle
     import synth
 
+    cap = 16_000_000
     gd = None if w.gdtype == "f32" else w.gdtype
-    spent, params, layers_done = 0.0, 0, []
-    order = sorted(range(len(w.layers)), key=lambda li: -w.layer_elems(li))
-    # start from a mid-sized layer: the largest one alone could exceed the budget
-    order = [li for li in order if w.layer_elems(li) <= 40_000_000] or order[-1:]
-    for li in order:
+    spent, params, layers_done, capped = 0.0, 0, 0, False
+    for li in sorted(range(len(w.layers)), key=lambda li: -w.layer_elems(li)):
         if spent >= budget_s:
             break
         for ti in w.layers[li]:
-            n = w.tensors[ti].n
+            if spent >= budget_s:
+                break
+            n = min(w.tensors[ti].n, cap)
+            capped = capped or n < w.tensors[ti].n
             theta = synth.fill_host(w.theta_spec(ti), "f32", n).astype(np.float64)
             m = np.zeros(n)
             v = np.zeros(n)
@@ -88,11 +91,12 @@ def cpu_baseline(w, budget_s: float = 15.0, optimizer: str = "adama") -> dict:
                     oracle.apply(theta, m, v, w.lr, w.eps, w.beta1, w.beta2, 1)
             spent += time.perf_counter() - t0
             params += n
-        layers_done.append(li)
+        layers_done += 1
     per_param = per_param_bytes(w, optimizer)
     return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "params_per_s": round(params / spent, 1),
-            "sample": f"{len(layers_done)} whole layer(s) of {w.name} ({params} params), one full mini-batch "
+            "sample": f"tensors of the {layers_done} largest layer(s) of {w.name} ({params} params"
+                      f"{', at most the first 16 M elements of each' if capped else ''}), one full mini-batch "
                       f"each (decay + {w.N} folds + update) in {spent:.1f} s, single thread, fp64"}
 
 
@@ -131,7 +135,7 @@ def cpu_baseline_all_cores(w, budget_s: float = 8.0, optimizer: str = "adama") -
         for t in big:
             if spent >= budget_s:
                 break
-            n = t.n
+            n = min(t.n, 32_000_000)
             theta = synth.fill_host(w.theta_spec(t.index), "f32", n).astype(np.float64)
             m, v = np.zeros(n), np.zeros(n)
             grads = [synth.fill_host(w.grad_spec(1, i, t.index), w.gdtype, n) for i in range(min(w.N, 2))]
