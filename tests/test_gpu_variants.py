@@ -336,3 +336,65 @@ def test_full_size_c3_variants_sampled(torch_cuda, optimizer):
 
     gc.collect()
     torch_cuda.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------
+# 16-bit gradient patterns and non-finite values through the SGD fold and the scaled Adam fold
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("gdt", ["f16", "bf16"])
+def test_sgdm_fold_every_16_bit_pattern(torch_cuda, gdt):
+    """Every finite pattern (fp16 subnormals included; bf16 within a range whose sums stay normal)
+    through one SGD fold from a zero buffer: b = s * g / N up to one float32 rounding."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    if gdt == "f16":
+        val = bits.view(np.float16).astype(np.float64)
+        keep = np.isfinite(val)
+    else:
+        with np.errstate(invalid="ignore"):            # signalling-NaN patterns are filtered out just below
+            val = (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+        keep = np.isfinite(val) & (np.abs(val) < 1e30) & ((np.abs(val) > 1e-30) | (val == 0))
+    bits, val = bits[keep], val[keep]
+    n = bits.size
+    g = torch.from_numpy(bits.view(np.int16).copy()).cuda()
+    b = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    N, scale = 3, 0.5
+    binding.adama_sgdm_fold_multi([(None, b, g, n)], None, gdt, N, (0.0, scale))
+    torch.cuda.synchronize()
+    ref = np.zeros(n)
+    oracle.sgdm_fold(ref, bits, N, scale, gdtype=gdt)
+    got = b.cpu().numpy().astype(np.float64)
+    nz = ref != 0
+    assert np.all(got[~nz] == 0)
+    assert np.all(np.sign(got[nz]) == np.sign(ref[nz]))
+    assert np.max(np.abs(got[nz] - ref[nz]) / np.abs(ref[nz])) <= 2.0 ** -22
+
+
+def test_non_finite_gradients_propagate_through_the_variants(torch_cuda):
+    """inf and NaN gradients follow IEEE rules in the SGD buffer and in the scaled Adam fold; finite
+    neighbours are untouched."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n = 4099
+    g = torch.full((n,), 0.25, dtype=torch.float32, device="cuda:0")
+    g[5], g[1000], g[4098] = float("inf"), float("-inf"), float("nan")
+    b = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    th = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    binding.adama_sgdm_fold_multi([(None, b, g, n)], None, "f32", 2)
+    binding.adama_sgdm_apply_multi([(th, b, None, n)], None, 0.5)
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    binding.adama_fold_opt_multi([(m, v, g, n)], None, "f32", 2, B1, B2, (0.0, 0.5))
+    torch.cuda.synchronize()
+    hb, ht, hm, hv = (x.cpu().numpy() for x in (b, th, m, v))
+    assert hb[5] == np.inf and hb[1000] == -np.inf and np.isnan(hb[4098])
+    assert ht[5] == -np.inf and ht[1000] == np.inf and np.isnan(ht[4098])
+    assert hm[5] == np.inf and hm[1000] == -np.inf and np.isnan(hm[4098])
+    assert hv[5] == np.inf and hv[1000] == np.inf and np.isnan(hv[4098])
+    fin = np.ones(n, dtype=bool)
+    fin[[5, 1000, 4098]] = False
+    assert np.all(hb[fin] == 0.125) and np.all(ht[fin] == 1.0 - 0.5 * 0.125)
+    assert np.allclose(hm[fin], (1 - B1) * 0.25 * 0.5 / 2, rtol=1e-6) and np.allclose(hv[fin], (1 - B2) * (0.25 * 0.5 / 2) ** 2, rtol=1e-6)
