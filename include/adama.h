@@ -161,7 +161,7 @@ adama_status adama_rescale_apply_multi(const adama_state *list, int count, doubl
                                        double eps, double beta1, double beta2, long long t, hipStream_t stream);
 
 /* ------------------------------------------------------------------------------------------------
- * Variants.  The paper's Conclusion notes that the same scheme -- fold each gradient into the
+ * Variants.  The paper's Discussion (Sec. 5) notes that the same scheme -- fold each gradient into the
  * optimizer state as it is produced, then release it -- serves any momentum-based optimizer.  The
  * calls below carry it to Adam with decoupled weight decay (AdamW), to gradients taken on a scaled
  * loss (mixed-precision loss scaling), and to SGD with momentum.  The paper gives no formulas for

@@ -21,7 +21,7 @@
  * independence; exhaustive bf16/fp16 widening against library conversions.
  *
  * The last part of the file carries the technique over to the variants the
- * paper's conclusion points at (any momentum-based optimizer can fold and
+ * paper's discussion (Sec. 5) points at (any momentum-based optimizer can fold and
  * release gradients the same way): a loss-scale factor on the gradient,
  * decoupled weight decay in the update (AdamW), and SGD with momentum.  The
  * paper gives no formulas for these; each follows the optimizer's textbook
@@ -193,7 +193,7 @@ void adama_oracle_ddp_combine(double *m_out, double *v_out, const double *m_rank
 }
 
 /* ================================================================== */
-/* Variants beyond the paper's algorithm boxes (Conclusion: the same    */
+/* Variants beyond the paper's algorithm boxes (Discussion: the same    */
 /* fold-and-release works for any momentum-based optimizer).            */
 /* ================================================================== */
 

@@ -121,7 +121,7 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 //                                             = theta - lr*m_hat/(sqrt(v_hat)+eps); IEEE sqrt and divide
 //   rescale_apply (Sec. 3.3, after Eq. 5):    m <- m/M, v <- v/M^2 on the all-reduced sums, then apply
 //
-// Variants the paper's Conclusion points at (the same scheme for other momentum-based optimizers):
+// Variants the paper's Discussion (Sec. 5) points at (the same scheme for other momentum-based optimizers):
 //   decoupled weight decay:  theta <- theta - (lr*lambda*theta + Adam step); the two are summed first
 //                            so theta is rounded once.  With wd == 0 the plain expression is selected,
 //                            bit for bit.

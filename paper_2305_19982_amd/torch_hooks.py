@@ -162,7 +162,7 @@ class AdamAccumulation(_HookedAccumulation):
 
 
 class MomentumAccumulation(_HookedAccumulation):
-    """SGD with momentum accumulated the AdamA way (the paper's Conclusion): the momentum buffer takes
+    """SGD with momentum accumulated the AdamA way (the paper's Discussion, Sec. 5): the momentum buffer takes
     each layer's gradient of each micro-batch as it is produced, and the gradient is released.  The
     result is the textbook step b <- mu b + mean gradient, theta <- theta - lr b (plus decoupled weight
     decay, if any) up to rounding.  Protocol and arguments as AdamAccumulation."""
