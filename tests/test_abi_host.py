@@ -332,3 +332,48 @@ def test_geometry_walk_flags_nothing_on_workload_shapes(lib):
                 goff += n
             for op in (1, 3, 4, 7, 9, 10):
                 _walk_and_check(entries, op, w.gdtype)
+
+
+def test_geometry_randomised_lists(lib):
+    """Seeded random tensor lists with adversarial lengths (around multiples of every chunk size, zero,
+    tiny), random misalignments of every array and random co-alignment, for every op and gradient
+    format, below and above the large-launch threshold: every element exactly once, in bounds, vector
+    accesses aligned."""
+    rng = np.random.default_rng(20240607)
+    chunks = (512, 1024, 2048, 4096)
+    gdts = (("f32", 4), ("bf16", 2), ("f16", 2))
+    for trial in range(66):
+        op = trial % 11
+        gdt, gb = gdts[(trial // 11) % 3]
+        big = trial % 2 == 0
+        entries, total = [], 0
+        count = int(rng.integers(1, 30))
+        for i in range(count):
+            kind = int(rng.integers(0, 5))
+            if kind == 0:
+                n = int(rng.integers(0, 6))
+            elif kind == 1:
+                n = int(rng.choice(chunks)) * int(rng.integers(1, 6)) + int(rng.integers(-3, 4))
+            elif kind == 2:
+                n = int(rng.integers(1, 40000))
+            elif kind == 3:
+                n = int(rng.choice(chunks)) - int(rng.integers(0, 4))
+            else:
+                n = int(rng.integers(100000, 400000)) if big else int(rng.integers(1, 3000))
+            n = max(n, 0)
+            pre = [int(rng.integers(0, 4)) for _ in range(4)]
+            if rng.integers(0, 3) > 0:                # two thirds of the tensors co-aligned
+                pre = [pre[0]] * 4
+            base = FAKE + (i << 26)
+            entries.append((base + (1 << 40) + 4 * pre[0], base + (2 << 40) + 4 * pre[1], base + (3 << 40) + 4 * pre[2],
+                            base + (4 << 40) + gb * pre[3], n))
+            total += n
+        if big and total < (1 << 20):
+            entries.append((FAKE + (5 << 40) + 4, FAKE + (6 << 40) + 4, FAKE + (7 << 40) + 4, FAKE + (8 << 40) + gb,
+                            (1 << 20) + int(rng.integers(0, 5000))))
+        touched, nvec, nsc, launches = binding.adama_debug_walk(entries, op, gdt)
+        for k, (tch, e) in enumerate(zip(touched, entries)):
+            arr = np.frombuffer(tch, dtype=np.uint8)
+            assert arr.size == e[4] and np.all(arr == 1), f"trial {trial} op {op} {gdt} tensor {k} (n={e[4]})"
+        assert nvec * 4 + nsc == sum(e[4] for e in entries)
+        assert launches == 1
