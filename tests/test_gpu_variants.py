@@ -398,3 +398,41 @@ def test_non_finite_gradients_propagate_through_the_variants(torch_cuda):
     fin[[5, 1000, 4098]] = False
     assert np.all(hb[fin] == 0.125) and np.all(ht[fin] == 1.0 - 0.5 * 0.125)
     assert np.allclose(hm[fin], (1 - B1) * 0.25 * 0.5 / 2, rtol=1e-6) and np.allclose(hv[fin], (1 - B2) * (0.25 * 0.5 / 2) ** 2, rtol=1e-6)
+
+
+@pytest.mark.parametrize("gdt", ["f32", "bf16"])
+def test_sgdm_arrays_with_different_misalignments(torch_cuda, gdt):
+    """theta, b and the gradient each start a different number of elements past a 16-byte boundary, so
+    no 16-byte access is possible and every element goes through the element-wise path; long enough for
+    the large-launch shapes."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    gbytes = synth.gen.DTYPE_BYTES[gdt]
+    for n in (5, 1023, 70001, (1 << 20) + 77):
+        pad = 16
+        th = torch.zeros(n + pad, dtype=torch.float32, device="cuda:0")
+        b = torch.zeros(n + pad, dtype=torch.float32, device="cuda:0")
+        g = torch.zeros((n + pad) * gbytes, dtype=torch.uint8, device="cuda:0")
+        o_t, o_b, o_g = 1, 2, 3
+        th0 = synth.fill_host(synth.Spec(key=synth.stream_key(67, n), sigma=0.05), "f32", n)
+        th[o_t:o_t + n] = torch.from_numpy(th0).cuda()
+        spec = synth.Spec(key=synth.stream_key(67, n, 1), sigma=1e-2, p_zero=0.02)
+        synth.fill_device(g.data_ptr() + gbytes * o_g, spec, gdt, n, 0)
+        lst = [(th.data_ptr() + 4 * o_t, b.data_ptr() + 4 * o_b, g.data_ptr() + gbytes * o_g, n)]
+        N, mu, lr, wd = 2, 0.9, 0.05, 0.1
+        binding.adama_sgdm_fold_first_multi(lst, None, gdt, N, mu)
+        binding.adama_sgdm_fold_last_apply_multi(lst, None, gdt, N, lr, (wd, 1.0))
+        torch.cuda.synchronize()
+        rb, rt = np.zeros(n), th0.astype(np.float64)
+        gh = synth.fill_host(spec, gdt, n)
+        gd = None if gdt == "f32" else gdt
+        oracle.sgdm_begin_step(rb, mu)
+        oracle.sgdm_fold(rb, gh, N, 1.0, gdtype=gd)
+        oracle.sgdm_fold(rb, gh, N, 1.0, gdtype=gd)
+        oracle.sgdm_apply(rt, rb, lr, wd)
+        name = f"sgdm misaligned {gdt} n={n}"
+        check_close(name, "m", b[o_b:o_b + n].cpu().numpy(), rb)
+        check_close(name, "theta", th[o_t:o_t + n].cpu().numpy(), rt, th0, th0.astype(np.float64))
+        for arr, o in ((th, o_t), (b, o_b)):
+            assert float(arr[:o].abs().sum()) == 0.0 and float(arr[o + n:].abs().sum()) == 0.0, name
