@@ -642,19 +642,24 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
                 const Desc &d = b.tab.t[k];
                 const uint64_t lc = c - b.tab.chunk_start[k];
                 const uint32_t pre = misalign_elems(d.s[0]);
-                const bool vec = coaligned(d, ns, gb);
+                const bool aligned = coaligned(d, ns, gb);
                 unsigned char *tch = touched[base + (int)k];
-                const bool interior = chunk_is_interior(vec, pre, d.n, lc, chunk);
+                const bool interior = chunk_is_interior(pre, d.n, lc, chunk);
                 for (int u = 0; u < b.shape.u; ++u) {
                     for (uint32_t tid = 0; tid < (uint32_t)b.shape.block; ++tid) {
                         const uint64_t coord = lc * chunk + (uint64_t)(u * b.shape.block + tid) * kGroup;
-                        const int kind = interior ? 2 : group_kind(vec, pre, d.n, coord);
+                        const int kind = interior ? 2 : group_kind(pre, d.n, coord);
                         if (kind == 2) {
                             if (coord < pre) return fail(ADAMA_ERR_INVALID_ARG, "vector access before tensor %d", base + (int)k);
                             const uint64_t e = coord - pre;
                             if (e + kGroup > d.n) return fail(ADAMA_ERR_INVALID_ARG, "vector access past tensor %d", base + (int)k);
-                            bool ok = gb == 0 || aligned_to((const char *)d.g + e * gb, 4 * gb);
-                            for (int a = 0; a < ns; ++a) ok = ok && aligned_to((const float *)d.s[a] + e, 16);
+                            // the first state array is always reached on a 16-byte boundary; the others
+                            // too when the tensor is co-aligned (then the kernel declares them aligned)
+                            bool ok = aligned_to((const float *)d.s[0] + e, 16);
+                            if (aligned) {
+                                ok = ok && (gb == 0 || aligned_to((const char *)d.g + e * gb, 4 * gb));
+                                for (int a = 1; a < ns; ++a) ok = ok && aligned_to((const float *)d.s[a] + e, 16);
+                            }
                             if (!ok) return fail(ADAMA_ERR_INVALID_ARG, "misaligned vector access in tensor %d", base + (int)k);
                             for (int j = 0; j < kGroup; ++j) ++tch[e + j];
                             ++nvec;

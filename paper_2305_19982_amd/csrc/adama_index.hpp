@@ -5,11 +5,12 @@
 // tensor sits at coordinate pre + e, where pre (0..3) is the number of float32
 // elements by which the tensor's first state array is past a 16-byte boundary.
 // Coordinates that are multiples of 4 therefore fall on 16-byte boundaries of
-// the state arrays, whatever the tensor's start address.  When the other
-// arrays of the tensor share that misalignment ("co-aligned"), every 4-element
-// group wholly inside the tensor can be moved with 16-byte accesses; the at
-// most one partial group at either end, and tensors that are not co-aligned,
-// are moved element by element.
+// the first state array, whatever the tensor's start address.  Every 4-element
+// group wholly inside the tensor is moved with one wide access per array:
+// aligned when the other arrays of the tensor share that misalignment
+// ("co-aligned"), otherwise declared with element alignment only, which the
+// hardware serves by splitting an access where it straddles a boundary.  The at
+// most one partial group at either end is moved element by element.
 #pragma once
 
 #include <stdint.h>
@@ -130,20 +131,19 @@ ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t c)
 }
 
 // Chunk lc of a tensor covers coordinates [lc*chunk, (lc+1)*chunk).  It is "interior" when the
-// tensor is co-aligned and the whole coordinate range lies inside [pre, pre+n): then every group
-// of the chunk is a full, 16-byte aligned group.
-ADAMA_HD bool chunk_is_interior(bool vec, uint32_t pre, uint64_t n, uint64_t lc, uint32_t chunk)
+// whole coordinate range lies inside [pre, pre+n): then every group of the chunk is a full group.
+ADAMA_HD bool chunk_is_interior(uint32_t pre, uint64_t n, uint64_t lc, uint32_t chunk)
 {
     uint64_t lo = lc * chunk;
-    return vec && lo >= pre && lo + chunk <= pre + n;
+    return lo >= pre && lo + chunk <= pre + n;
 }
 
-// How the group at coordinate `coord` (a multiple of 4) is moved: 2 = one 16-byte access per array,
+// How the group at coordinate `coord` (a multiple of 4) is moved: 2 = one wide access per array,
 // 1 = element by element (only elements inside the tensor), 0 = nothing to do.
-ADAMA_HD int group_kind(bool vec, uint32_t pre, uint64_t n, uint64_t coord)
+ADAMA_HD int group_kind(uint32_t pre, uint64_t n, uint64_t coord)
 {
     if (coord + kGroup <= pre || coord >= pre + n) return 0;
-    if (vec && coord >= pre && coord + kGroup <= pre + n) return 2;
+    if (coord >= pre && coord + kGroup <= pre + n) return 2;
     return 1;
 }
 

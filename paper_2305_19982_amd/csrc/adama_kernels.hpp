@@ -37,6 +37,12 @@ namespace adama {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+// The same vectors declared with the alignment of one element only.  The compiler still emits one
+// wide memory instruction for them on this target (unaligned global accesses are part of the HSA
+// memory model); it would split them itself on a target without that guarantee.
+typedef float f32x4_u __attribute__((ext_vector_type(4), aligned(4)));
+typedef uint32_t u32x2_u __attribute__((ext_vector_type(2), aligned(2)));
+typedef _Float16 f16x4_u __attribute__((ext_vector_type(4), aligned(2)));
 
 enum GradType : int { kF32 = 0, kBF16 = 1, kF16 = 2 };
 
@@ -82,6 +88,7 @@ template <int GT> struct Grad;
 
 template <> struct Grad<kF32> {
     using Vec = f32x4;
+    using VecU = f32x4_u;
     using Elem = float;
     static __device__ __forceinline__ f32x4 widen(f32x4 g) { return g; }
     static __device__ __forceinline__ float widen1(float g) { return g; }
@@ -89,6 +96,7 @@ template <> struct Grad<kF32> {
 
 template <> struct Grad<kBF16> {   // bfloat16 is the upper half of a float32 word
     using Vec = u32x2;
+    using VecU = u32x2_u;
     using Elem = uint16_t;
     static __device__ __forceinline__ f32x4 widen(u32x2 w)
     {
@@ -104,6 +112,7 @@ template <> struct Grad<kBF16> {   // bfloat16 is the upper half of a float32 wo
 
 template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals included
     using Vec = f16x4;
+    using VecU = f16x4_u;
     using Elem = _Float16;
     static __device__ __forceinline__ f32x4 widen(f16x4 h) { return __builtin_convertvector(h, f32x4); }
     static __device__ __forceinline__ float widen1(_Float16 h) { return (float)h; }
@@ -151,17 +160,25 @@ __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars
     }
 }
 
-// ---- one interior chunk: every group is a full aligned group; all loads first ----
-template <int OpK, int GT, int BLOCK, int U, int NT>
+// Picks the aligned or the element-aligned flavour of a vector type.
+template <bool ALIGNED, typename A, typename U_> struct Pick { using T = A; };
+template <typename A, typename U_> struct Pick<false, A, U_> { using T = U_; };
+
+// ---- one interior chunk: every group is a full group; all loads first ----
+// ALIGNED: the tensor's arrays are co-aligned, so every access falls on a 16-byte boundary (8-byte for
+// 16-bit gradients); otherwise the accesses are declared element-aligned.
+template <int OpK, int GT, int BLOCK, int U, int NT, bool ALIGNED>
 __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint32_t tid, const Scalars &sc)
 {
     constexpr bool ntg = (NT & kNtGradLoad) != 0, ntl = (NT & kNtStateLoad) != 0, nts = (NT & kNtStore) != 0;
     constexpr int NS = op_states(OpK);
     using G = Grad<GT>;
-    ADAMA_GLOBAL f32x4 *S[NS];
+    using SV = typename Pick<ALIGNED, f32x4, f32x4_u>::T;
+    using GV = typename Pick<ALIGNED, typename G::Vec, typename G::VecU>::T;
+    ADAMA_GLOBAL SV *S[NS];
 #pragma unroll
-    for (int k = 0; k < NS; ++k) S[k] = global_ptr<f32x4>(d.s[k], e0 * 4);
-    const ADAMA_GLOBAL typename G::Vec *Gp = global_ptr<typename G::Vec>(d.g, e0 * sizeof(typename G::Elem));
+    for (int k = 0; k < NS; ++k) S[k] = global_ptr<SV>(d.s[k], e0 * 4);
+    const ADAMA_GLOBAL GV *Gp = global_ptr<GV>(d.g, e0 * sizeof(typename G::Elem));
     typename G::Vec g[U];
     f32x4 x[NS][U];
     // All loads first, then, group by group, arithmetic and stores: a group's stores are issued as soon
@@ -193,25 +210,31 @@ __device__ __forceinline__ void interior_chunk(const Desc &d, uint64_t e0, uint3
         }
 #pragma unroll
         for (int k = 0; k < NS; ++k)
-            if ((op_store_mask(OpK) >> k) & 1) st<nts>(S[k] + i, x[k][u]);
+            if ((op_store_mask(OpK) >> k) & 1) st<nts>(S[k] + i, (SV)x[k][u]);
     }
 }
 
-// ---- one group of a boundary chunk: a full aligned group, or element by element ----
+// ---- one group of a boundary chunk: a full group (one wide access per array), or element by element ----
 template <int OpK, int GT>
-__device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t pre, uint64_t coord, const Scalars &sc)
+__device__ __forceinline__ void boundary_group(const Desc &d, bool aligned, uint32_t pre, uint64_t coord, const Scalars &sc)
 {
     constexpr int NS = op_states(OpK);
     using G = Grad<GT>;
-    const int kind = group_kind(vec, pre, d.n, coord);
+    const int kind = group_kind(pre, d.n, coord);
     if (kind == 0) return;
     if (kind == 2) {
         const uint64_t e = coord - pre;
         f32x4 x[NS];
-#pragma unroll
-        for (int k = 0; k < NS; ++k) x[k] = *global_ptr<f32x4>(d.s[k], e * 4);
         f32x4 gf = {0.0f, 0.0f, 0.0f, 0.0f};
-        if constexpr (op_has_grad(OpK)) gf = G::widen(*global_ptr<typename G::Vec>(d.g, e * sizeof(typename G::Elem)));
+        if (aligned) {
+#pragma unroll
+            for (int k = 0; k < NS; ++k) x[k] = *global_ptr<f32x4>(d.s[k], e * 4);
+            if constexpr (op_has_grad(OpK)) gf = G::widen(*global_ptr<typename G::Vec>(d.g, e * sizeof(typename G::Elem)));
+        } else {
+#pragma unroll
+            for (int k = 0; k < NS; ++k) x[k] = *global_ptr<f32x4_u>(d.s[k], e * 4);
+            if constexpr (op_has_grad(OpK)) gf = G::widen(*global_ptr<typename G::VecU>(d.g, e * sizeof(typename G::Elem)));
+        }
 #pragma unroll
         for (int j = 0; j < kGroup; ++j) {
             float el[3] = {0.0f, 0.0f, 0.0f};
@@ -223,7 +246,10 @@ __device__ __forceinline__ void boundary_group(const Desc &d, bool vec, uint32_t
         }
 #pragma unroll
         for (int k = 0; k < NS; ++k)
-            if ((op_store_mask(OpK) >> k) & 1) *global_ptr<f32x4>(d.s[k], e * 4) = x[k];
+            if ((op_store_mask(OpK) >> k) & 1) {
+                if (aligned) *global_ptr<f32x4>(d.s[k], e * 4) = x[k];
+                else *global_ptr<f32x4_u>(d.s[k], e * 4) = (f32x4_u)x[k];
+            }
         return;
     }
 #pragma unroll
@@ -265,13 +291,14 @@ __global__ void __launch_bounds__(BLOCK) multi_tensor_kernel(const Table<kMaxTen
     const Desc d = tab.t[k];
     const uint64_t lc = SINGLE ? c : c - tab.chunk_start[k];
     const uint32_t pre = misalign_elems(d.s[0]);
-    const bool vec = coaligned(d, op_states(OpK), g_bytes);
-    if (chunk_is_interior(vec, pre, d.n, lc, chunk)) {
-        interior_chunk<OpK, GT, BLOCK, U, NT>(d, lc * chunk - pre, tid, sc);
+    const bool aligned = coaligned(d, op_states(OpK), g_bytes);
+    if (chunk_is_interior(pre, d.n, lc, chunk)) {
+        if (aligned) interior_chunk<OpK, GT, BLOCK, U, NT, true>(d, lc * chunk - pre, tid, sc);
+        else interior_chunk<OpK, GT, BLOCK, U, NT, false>(d, lc * chunk - pre, tid, sc);
     } else {
 #pragma unroll 1
         for (int u = 0; u < U; ++u)
-            boundary_group<OpK, GT>(d, vec, pre, lc * chunk + (uint64_t)(u * BLOCK + tid) * kGroup, sc);
+            boundary_group<OpK, GT>(d, aligned, pre, lc * chunk + (uint64_t)(u * BLOCK + tid) * kGroup, sc);
     }
 }
 
