@@ -2,7 +2,6 @@
 header declares, rejects bad arguments before touching the device, treats empty inputs as no-ops,
 and its launch geometry covers every element of every tensor exactly once with in-bounds,
 aligned accesses."""
-import ctypes
 import os
 import re
 
