@@ -1,6 +1,7 @@
 """End-to-end demonstration of the paper's system claim on PyTorch-ROCm: a GPT-style transformer on
-synthetic tokens trained with (a) plain gradient accumulation + Adam and (b) AdamA through backward
-hooks (torch_hooks.AdamAccumulation), same model, same micro-batches.
+synthetic tokens trained with (a) plain gradient accumulation + Adam, (b) AdamA through backward
+hooks (torch_hooks.AdamAccumulation) and (c) the same with the folds on a side stream, same model,
+same micro-batches.
 
     python -m paper_2305_19982_amd.hook_demo [--layers 24] [--hidden 2048] [--heads 16] [--seq 1024]
                                              [--micro-batch 4] [--N 8] [--steps 3]
@@ -71,25 +72,27 @@ def run(mode: str, args, data) -> dict:
     torch.manual_seed(0)
     model = TinyGPT(args.layers, args.hidden, args.heads, args.vocab, args.seq).cuda()
     n_params = sum(p.numel() for p in model.parameters())
-    if mode == "adama":
-        opt = AdamAccumulation(block_layers(model), lr=1e-4, N=args.N, fused_edges=True)
+    adama = mode.startswith("adama")
+    if adama:
+        opt = AdamAccumulation(block_layers(model), lr=1e-4, N=args.N, fused_edges=True,
+                               overlap=mode == "adama_overlap")
     else:
         opt = torch.optim.Adam(model.parameters(), lr=1e-4, fused=True)
 
     def mini_batch(batch):
-        if mode == "adama":
+        if adama:
             opt.begin_mini_batch()
         for tokens in batch:
             with torch.autocast("cuda", dtype=torch.bfloat16):
                 logits = model(tokens[:, :-1])
             loss = F.cross_entropy(logits.float().view(-1, logits.shape[-1]), tokens[:, 1:].reshape(-1))
-            if mode == "adama":
+            if adama:
                 loss.backward()                    # raw gradients: the fold applies 1/N
                 opt.micro_batch_done()
             else:
                 (loss / args.N).backward()         # accumulate into p.grad
         opt.step()
-        if mode != "adama":
+        if not adama:
             opt.zero_grad(set_to_none=True)
         return loss
 
@@ -107,7 +110,7 @@ def run(mode: str, args, data) -> dict:
     out = {"step_ms": round(dt * 1e3, 2), "tokens_per_s": round(tokens / dt, 1), "params": n_params,
            "resident_bytes": base, "peak_bytes": peak, "peak_over_resident_bytes": peak - base,
            "final_loss": round(float(loss.detach()), 4)}
-    if mode == "adama":
+    if adama:
         out["peak_live_grad_bytes"] = opt.peak_live_grad_bytes
         opt.remove_hooks()
     del model, opt
@@ -122,11 +125,14 @@ def compare(args) -> dict:
              for _ in range(args.N)] for _ in range(args.steps + 1)]
     accum = run("accumulation", args, data)
     adama = run("adama", args, data)
+    over = run("adama_overlap", args, data)
     return {
         "model": {"layers": args.layers, "hidden": args.hidden, "heads": args.heads, "seq": args.seq,
                   "micro_batch": args.micro_batch, "N": args.N, "params": accum["params"]},
-        "gradient_accumulation_adam": accum, "adama_hooks": adama,
+        "gradient_accumulation_adam": accum, "adama_hooks": adama, "adama_hooks_side_stream": over,
         "throughput_ratio": round(adama["tokens_per_s"] / accum["tokens_per_s"], 4),
+        "throughput_ratio_side_stream": round(over["tokens_per_s"] / accum["tokens_per_s"], 4),
+        "peak_memory_saved_frac_side_stream": round(1.0 - over["peak_bytes"] / accum["peak_bytes"], 4),
         "peak_memory_saved_bytes": accum["peak_bytes"] - adama["peak_bytes"],
         "peak_memory_saved_frac": round(1.0 - adama["peak_bytes"] / accum["peak_bytes"], 4),
         "data": "synthetic tokens"}

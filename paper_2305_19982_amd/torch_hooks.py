@@ -38,11 +38,20 @@ class _HookedAccumulation:
     backward pass, fold the layer with one launch when the last one has arrived, release the gradients.
 
     Subclasses provide the state (`_alloc_state`) and the three kinds of launches (`_decay_all`,
-    `_fold`, `_apply_all`)."""
+    `_fold`, `_apply_all`).
+
+    overlap=True queues every optimizer launch on a side stream (default priority) instead of the
+    stream autograd runs on: a layer's fold waits for an event recorded when its gradients are complete
+    and then runs next to the backward kernels of the following layers, so the memory-bound fold hides
+    behind compute-bound work.  The gradients are handed to the side stream with record_stream(), which
+    keeps the allocator from reusing their memory before the fold has read them; step() makes the
+    autograd stream wait for the side stream, so the next forward pass sees the updated parameters."""
 
     def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], N: int, fused_edges: bool,
-                 weight_decay: float, grad_scale: float):
+                 weight_decay: float, grad_scale: float, overlap: bool = False):
         binding.load()
+        self.overlap = bool(overlap)
+        self._side = None
         self.N = int(N)
         self.fused_edges = bool(fused_edges) and self.N > 1
         self._opt = None if (weight_decay == 0.0 and grad_scale == 1.0) else binding.options(weight_decay, grad_scale)
@@ -67,13 +76,26 @@ class _HookedAccumulation:
                 self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
             self._pending.append(len(ps))
 
+    # ---- streams ----
+    def _launch_stream(self) -> int:
+        """The stream optimizer launches go to, ordered after everything queued so far on the current one."""
+        cur = torch.cuda.current_stream()
+        if not self.overlap:
+            return cur.cuda_stream
+        if self._side is None:
+            self._side = torch.cuda.Stream(device=cur.device)
+        ev = torch.cuda.Event()
+        ev.record(cur)
+        self._side.wait_event(ev)
+        return self._side.cuda_stream
+
     # ---- the mini-batch protocol ----
     def begin_mini_batch(self) -> None:
         """t <- t+1 and the moment decay (deferred into the first micro-batch's folds when fused)."""
         self.t += 1
         self.micro = 0
         if not self.fused_edges:
-            self._decay_all(torch.cuda.current_stream().cuda_stream)
+            self._decay_all(self._launch_stream())
 
     def _on_grad(self, p: torch.nn.Parameter) -> None:
         li = self._layer_of[p]
@@ -91,8 +113,11 @@ class _HookedAccumulation:
             raise ValueError("gradients of one layer must share a dtype")
         first = self.fused_edges and self.micro == 0
         last = self.fused_edges and self.micro == self.N - 1
-        self._fold(ps, grads, gdt, first, last, torch.cuda.current_stream().cuda_stream)
-        for p in ps:                                   # release: the fold is queued on the producing stream
+        self._fold(ps, grads, gdt, first, last, self._launch_stream())
+        if self.overlap:
+            for g in grads:                            # the side stream still reads them
+                g.record_stream(self._side)
+        for p in ps:                                   # release: the fold is queued, stream order does the rest
             self._live_grad_bytes -= p.grad.numel() * p.grad.element_size()
             p.grad = None
         self._pending[li] = len(ps)
@@ -108,7 +133,9 @@ class _HookedAccumulation:
         if self.micro != self.N:
             raise RuntimeError(f"step() after {self.micro} of {self.N} micro-batches")
         if not self.fused_edges:
-            self._apply_all(torch.cuda.current_stream().cuda_stream)
+            self._apply_all(self._launch_stream())
+        if self.overlap and self._side is not None:
+            torch.cuda.current_stream().wait_stream(self._side)
 
     def remove_hooks(self) -> None:
         for h in self._handles:
@@ -131,10 +158,10 @@ class AdamAccumulation(_HookedAccumulation):
 
     def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-3,
                  betas: tuple = (0.9, 0.999), eps: float = 1e-8, N: int = 1, fused_edges: bool = True,
-                 weight_decay: float = 0.0, grad_scale: float = 1.0):
+                 weight_decay: float = 0.0, grad_scale: float = 1.0, overlap: bool = False):
         self.lr, self.beta1, self.beta2, self.eps = float(lr), float(betas[0]), float(betas[1]), float(eps)
         self.m, self.v = {}, {}
-        super().__init__(layers, N, fused_edges, weight_decay, grad_scale)
+        super().__init__(layers, N, fused_edges, weight_decay, grad_scale, overlap)
         self._state_list = binding.state_list(
             [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel()) for ps in self.layers for p in ps])
 
@@ -168,10 +195,11 @@ class MomentumAccumulation(_HookedAccumulation):
     decay, if any) up to rounding.  Protocol and arguments as AdamAccumulation."""
 
     def __init__(self, layers: Sequence[Iterable[torch.nn.Parameter]], lr: float = 1e-2, momentum: float = 0.9,
-                 N: int = 1, fused_edges: bool = True, weight_decay: float = 0.0, grad_scale: float = 1.0):
+                 N: int = 1, fused_edges: bool = True, weight_decay: float = 0.0, grad_scale: float = 1.0,
+                 overlap: bool = False):
         self.lr, self.momentum = float(lr), float(momentum)
         self.b = {}
-        super().__init__(layers, N, fused_edges, weight_decay, grad_scale)
+        super().__init__(layers, N, fused_edges, weight_decay, grad_scale, overlap)
         self._state_list = binding.sgdm_list(
             [(p.data_ptr(), self.b[p].data_ptr(), None, p.numel()) for ps in self.layers for p in ps])
 

@@ -243,3 +243,36 @@ def test_transformer_demo_saves_the_gradient_memory():
     assert out["peak_memory_saved_bytes"] > 0.6 * grad_bytes
     assert b["peak_live_grad_bytes"] < 0.5 * grad_bytes
     print(out, flush=True)
+
+
+def test_side_stream_folds_give_the_same_bits():
+    """overlap=True moves every optimizer launch to a side stream ordered by events; the arithmetic and
+    its order per element are unchanged, so parameters and moments are bit-identical."""
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import AdamAccumulation, MomentumAccumulation, leaf_layers
+
+    torch.backends.cuda.matmul.allow_tf32 = False
+    N, steps = 3, 3
+    data = _batches(torch, N, steps)
+    loss_fn = torch.nn.MSELoss()
+    for cls, kw, state in ((AdamAccumulation, dict(lr=1e-3, weight_decay=0.01), ("m", "v")),
+                           (MomentumAccumulation, dict(lr=0.05, momentum=0.9), ("b",))):
+        for fused in (False, True):
+            results = []
+            for overlap in (False, True):
+                model = _model(torch)
+                opt = cls(leaf_layers(model), N=N, fused_edges=fused, overlap=overlap, **kw)
+                for step in range(steps):
+                    opt.begin_mini_batch()
+                    for (x, y) in data[step]:
+                        loss_fn(model(x), y).backward()
+                        opt.micro_batch_done()
+                    opt.step()
+                torch.cuda.synchronize()
+                params = [p.detach().clone() for p in model.parameters()]
+                moments = [getattr(opt, k)[p].clone() for k in state for p in model.parameters()]
+                results.append(params + moments)
+                opt.remove_hooks()
+            for a, b in zip(*results):
+                assert torch.equal(a, b), f"{cls.__name__} fused={fused}: side-stream result differs"
