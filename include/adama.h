@@ -31,7 +31,9 @@
  *    any later operation on the same stream.
  *  - A gradient must not overlap m or v; tensors of one list must not overlap.
  *  - Hyper-parameters are doubles; derived scalars ((1-beta1)/N, (1-beta2)/N^2,
- *    1-beta^t, ...) are formed in double on the host and rounded to float once.
+ *    1-beta^t, ...) are formed in double on the host and rounded to float once.  Decay
+ *    factors, whose rounding error would compound from step to step, are applied as a
+ *    float32 pair hi + lo that represents the double to about 1e-15.
  *  - Length 0 / count 0 is a successful no-op.  Errors are reported by the return
  *    value, with a message available from adama_last_error(); nothing aborts.
  *    Argument errors are detected before any device work is queued.

@@ -305,10 +305,13 @@ void set_fold_scalars(Scalars &sc, int N, double beta1, double beta2, double gra
     sc.c2 = (float)((1.0 - beta2) * (grad_scale * grad_scale) / (dn * dn));
 }
 
+// A decay factor as float32 hi + lo, so that the factor the kernel applies is the double to about 1e-15.
 void set_decay_scalars(Scalars &sc, double beta1, double beta2)
 {
     sc.d1 = (float)beta1;
     sc.d2 = (float)beta2;
+    sc.d1lo = (float)(beta1 - (double)sc.d1);
+    sc.d2lo = (float)(beta2 - (double)sc.d2);
 }
 
 void set_apply_scalars(Scalars &sc, double lr, double eps, double beta1, double beta2, long long t)
@@ -556,7 +559,7 @@ adama_status adama_sgdm_begin_step_multi(const adama_sgdm_tensor *list, int coun
     ADAMA_TRY(check_sgdm_args(list, count, kSgdDecay, ADAMA_F32));
     if (!finite_nonneg(momentum)) return fail(ADAMA_ERR_INVALID_ARG, "momentum = %g must be finite and >= 0", momentum);
     Scalars sc{};
-    sc.d1 = (float)momentum;
+    set_decay_scalars(sc, momentum, 0.0);
     return run_sgdm(kSgdDecay, ADAMA_F32, list, count, sc, stream);
 }
 
@@ -583,8 +586,8 @@ adama_status adama_sgdm_fold_first_multi(const adama_sgdm_tensor *list, int coun
     Options o;
     ADAMA_TRY(read_options(opt, o));
     Scalars sc{};
+    set_decay_scalars(sc, momentum, 0.0);
     sc.c1 = (float)(o.grad_scale / (double)N);
-    sc.d1 = (float)momentum;
     return run_sgdm(kSgdFoldFirst, gdt, list, count, sc, stream);
 }
 

@@ -63,10 +63,11 @@ enum : int { kNtGradLoad = 1, kNtStateLoad = 2, kNtStore = 4 };
 //   c1 = (1-beta1)/N, c2 = (1-beta2)/N^2            fold, fold_first, fold_last_apply
 //        (with a gradient scale s: c1 = (1-beta1) s/N, c2 = (1-beta2) (s/N)^2;  SGD: c1 = s/N)
 //   d1 = beta1, d2 = beta2                           decay, fold_first (rescale_apply: 1/M, 1/M^2;  SGD: d1 = momentum)
+//   d1lo, d2lo = the part of each factor that float32 d1, d2 miss (factor - (double)d)
 //   step = lr/(1-beta1^t), rs2 = 1/sqrt(1-beta2^t), eps     apply, fold_last_apply, rescale_apply  (SGD: step = lr)
 //   wd = lr*lambda                                   decoupled weight decay of the updates; 0 = none
 struct Scalars {
-    float c1, c2, d1, d2, step, rs2, eps, wd;
+    float c1, c2, d1, d2, step, rs2, eps, wd, d1lo, d2lo;
 };
 
 template <bool NT, typename T>
@@ -123,7 +124,10 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 // Every product and sum below is rounded on its own (contraction is off), so a fused edge form
 // produces the very bits the separate steps would.
 //
-//   decay  (Alg. 2, first line of the loop):  m <- beta1*m, v <- beta2*v
+//   decay  (Alg. 2, first line of the loop):  m <- beta1*m, v <- beta2*v.  The factor is applied as
+//                                             hi*x + lo*x with hi = float32(beta), lo = beta - hi: float32(0.999)
+//                                             alone is 1.3e-8 too large, and since v averages over ~1000
+//                                             mini-batches that bias would compound to 1.3e-5 of v
 //   fold   (Alg. 2, inner body):              m <- m + c1*g, v <- v + c2*g^2   (g the raw gradient;
 //                                             g*g is exact in float32 for bf16 and fp16 inputs)
 //   apply  (Alg. 2, Update):                  theta <- theta - step*m / (sqrt(v)*rs2 + eps)
@@ -135,13 +139,22 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 //                            so theta is rounded once.  With wd == 0 the plain expression is selected,
 //                            bit for bit.
 //   SGD with momentum:       b <- mu*b;  b <- b + c1*g;  theta <- theta - (lr*lambda*theta + lr*b)
+// x * (hi + lo) with one rounding at x's magnitude: the small product is rounded first, the fused
+// multiply-add rounds the sum.  With lo == 0 (a factor float32 holds exactly) this is hi * x, also for
+// an infinite x.
+__device__ __forceinline__ float scale_hi_lo(float hi, float lo, float x)
+{
+    const float whole = __builtin_fmaf(hi, x, lo * x);
+    return lo != 0.0f ? whole : hi * x;
+}
+
 template <int OpK>
 __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars &sc)
 {
     constexpr int im = op_updates(OpK) ? 1 : 0, iv = im + 1;
     if constexpr (op_decays(OpK)) {
-        s[im] = sc.d1 * s[im];
-        if constexpr (!op_is_sgd(OpK)) s[iv] = sc.d2 * s[iv];
+        s[im] = scale_hi_lo(sc.d1, sc.d1lo, s[im]);
+        if constexpr (!op_is_sgd(OpK)) s[iv] = scale_hi_lo(sc.d2, sc.d2lo, s[iv]);
     }
     if constexpr (op_has_grad(OpK)) {
         s[im] = __builtin_fmaf(sc.c1, g, s[im]);

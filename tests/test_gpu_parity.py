@@ -575,3 +575,46 @@ def test_arena_placement_does_not_change_results(torch_cuda):
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
+
+
+def test_three_hundred_mini_batches_stay_within_tolerance(torch_cuda):
+    """Rounding errors of the float32 state do not build up beyond the tolerance over a long run: 300
+    mini-batches of 2 micro-batches (the second moment averages over about 1000 steps, so this is a third
+    of its memory), compared with the oracle after every 50th update."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n, N, steps = 8191, 2, 300
+    th = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    m = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+    g = torch.zeros(n, dtype=torch.bfloat16, device="cuda:0")
+    th0 = synth.fill_host(synth.Spec(key=synth.stream_key(83, 0), sigma=0.02), "f32", n)
+    th.copy_(torch.from_numpy(th0))
+    ref = oracle.OracleState([th0])
+    prev_gpu, prev_ref = th0.copy(), ref.theta[0].copy()
+    for t in range(1, steps + 1):
+        ref.begin_step(B1, B2)
+        for i in range(N):
+            spec = synth.Spec(key=synth.stream_key(83, t, i), sigma=3e-3, p_zero=0.01, p_outlier=0.001)
+            synth.fill_device(g.data_ptr(), spec, "bf16", n, 0)
+            if i == 0:
+                binding.adama_fold_first(m, v, g, "bf16", n, N, B1, B2)
+            else:
+                binding.adama_fold_last_apply(th, m, v, g, "bf16", n, N, LR, EPS, B1, B2, t)
+            ref.fold(0, synth.fill_host(spec, "bf16", n), N, B1, B2, gdtype="bf16")
+        ref.apply(LR, EPS, B1, B2)
+        if t % 50 == 0:
+            torch.cuda.synchronize()
+            name = f"long run t={t}"
+            sm = check_close(name, "m", m.cpu().numpy(), ref.m[0])
+            sv = check_close(name, "v", v.cpu().numpy(), ref.v[0])
+            got = th.cpu().numpy()
+            # theta itself: the binding criterion; its change over the last 50 steps on the change's own scale
+            err = np.abs(got.astype(np.float64) - ref.theta[0])
+            assert np.all(err <= np.maximum(1e-5 * np.abs(ref.theta[0]), 1e-6)), f"{name}: theta off by {err.max():.3e}"
+            d_gpu, d_ref = got.astype(np.float64) - prev_gpu, ref.theta[0] - prev_ref
+            scale = np.sqrt(np.mean(d_ref ** 2))
+            assert np.max(np.abs(d_gpu - d_ref)) <= 1e-5 * scale * 50 + 50 * 2.0 ** -24 * np.max(np.abs(got))
+            prev_gpu, prev_ref = got.astype(np.float64), ref.theta[0].copy()
+            _log(f"{name}: m {sm} v {sv} theta max abs err {err.max():.3e}")
