@@ -436,3 +436,56 @@ def test_sgdm_arrays_with_different_misalignments(torch_cuda, gdt):
         check_close(name, "theta", th[o_t:o_t + n].cpu().numpy(), rt, th0, th0.astype(np.float64))
         for arr, o in ((th, o_t), (b, o_b)):
             assert float(arr[:o].abs().sum()) == 0.0 and float(arr[o + n:].abs().sum()) == 0.0, name
+
+
+def test_long_run_of_the_variants_stays_within_tolerance(torch_cuda):
+    """300 mini-batches of AdamW with a gradient scale and of momentum SGD with weight decay: rounding
+    does not build up beyond the tolerance (the decay factors are applied as float32 pairs)."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    n, N, steps = 4099, 2, 300
+    for which in ("adamw", "sgdm"):
+        th = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+        a = torch.zeros(n, dtype=torch.float32, device="cuda:0")      # m or the momentum buffer
+        v = torch.zeros(n, dtype=torch.float32, device="cuda:0")
+        g = torch.zeros(n, dtype=torch.float16, device="cuda:0")
+        th0 = synth.fill_host(synth.Spec(key=synth.stream_key(89, 0), sigma=0.05), "f32", n)
+        th.copy_(torch.from_numpy(th0))
+        rt, ra, rv = th0.astype(np.float64), np.zeros(n), np.zeros(n)
+        scale, wd, lr, mu = 1.0 / 256.0, 0.05, 1e-3, 0.99
+        opt = (wd, scale)
+        for t in range(1, steps + 1):
+            if which == "adamw":
+                oracle.begin_step(ra, rv, B1, B2)
+            else:
+                oracle.sgdm_begin_step(ra, mu)
+            for i in range(N):
+                spec = synth.Spec(key=synth.stream_key(89, t, i), sigma=3e-3 / scale, outlier_scale=2.0, p_outlier=0.001)
+                synth.fill_device(g.data_ptr(), spec, "f16", n, 0)
+                gh = synth.fill_host(spec, "f16", n)
+                if which == "adamw":
+                    if i == 0:
+                        binding.adama_fold_first_opt_multi([(a, v, g, n)], None, "f16", N, B1, B2, opt)
+                    else:
+                        binding.adama_fold_last_apply_opt_multi([(th, a, v, g, n)], None, "f16", N, lr, EPS, B1, B2, t, opt)
+                    oracle.fold_scaled(ra, rv, gh, N, B1, B2, scale, gdtype="f16")
+                else:
+                    if i == 0:
+                        binding.adama_sgdm_fold_first_multi([(th, a, g, n)], None, "f16", N, mu, opt)
+                    else:
+                        binding.adama_sgdm_fold_last_apply_multi([(th, a, g, n)], None, "f16", N, lr, opt)
+                    oracle.sgdm_fold(ra, gh, N, scale, gdtype="f16")
+            if which == "adamw":
+                oracle.apply_adamw(rt, ra, rv, lr, EPS, B1, B2, t, wd)
+            else:
+                oracle.sgdm_apply(rt, ra, lr, wd)
+            if t % 100 == 0:
+                torch.cuda.synchronize()
+                name = f"long run {which} t={t}"
+                stats = [check_close(name, "m", a.cpu().numpy(), ra)]
+                if which == "adamw":
+                    stats.append(check_close(name, "v", v.cpu().numpy(), rv))
+                err = np.abs(th.cpu().numpy().astype(np.float64) - rt)
+                assert np.all(err <= np.maximum(1e-5 * np.abs(rt), 1e-6)), f"{name}: theta off by {err.max():.3e}"
+                print(name, stats, f"theta max abs err {err.max():.3e}", flush=True)
