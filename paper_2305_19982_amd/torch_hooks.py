@@ -8,9 +8,11 @@ into m and v on the stream autograd is running on, and the gradients are release
 (`p.grad = None` hands the memory back to the caching allocator, which reuses it for the next layer).
 Peak gradient memory is therefore about one layer instead of the whole model.
 
-PyTorch is the producer of gradients and the owner of memory here; theta is the parameters'
-own float32 storage, m and v are allocated by this class.  Gradients may be float32, bfloat16 or
-float16 (the dtype autograd produces for the parameter); parameters must be float32.
+PyTorch is the producer of gradients and the owner of memory here.  For float32 parameters theta is
+the parameters' own storage.  For bfloat16 / float16 parameters (whose gradients autograd produces in
+the same 16-bit format) this class keeps float32 master weights as theta, libadama updates those, and
+the 16-bit parameters are refreshed from them with a plain cast right after the update (that cast is
+the framework's weight refresh, not optimizer arithmetic).  m and v are always float32, allocated here.
 """
 from __future__ import annotations
 
@@ -58,6 +60,7 @@ class _HookedAccumulation:
         self.t = 0
         self.micro = 0
         self.layers = [list(ps) for ps in layers]
+        self.master = {}            # float32 master weights of 16-bit parameters
         self._layer_of = {}
         self._pending = []
         self._handles = []
@@ -69,12 +72,27 @@ class _HookedAccumulation:
                 if id(p) in seen:
                     raise ValueError("a parameter appears in two layers")
                 seen.add(id(p))
-                if p.dtype != torch.float32 or not p.is_cuda or not p.is_contiguous():
-                    raise ValueError("parameters must be contiguous float32 CUDA tensors")
+                if p.dtype not in _GDT or not p.is_cuda or not p.is_contiguous():
+                    raise ValueError("parameters must be contiguous float32, bfloat16 or float16 CUDA tensors")
+                if p.dtype != torch.float32:
+                    self.master[p] = p.detach().float()
                 self._alloc_state(p)
                 self._layer_of[p] = li
                 self._handles.append(p.register_post_accumulate_grad_hook(self._on_grad))
             self._pending.append(len(ps))
+
+    def _theta(self, p) -> torch.Tensor:
+        """The float32 array the update writes: the parameter itself, or its master copy."""
+        return self.master.get(p, p)
+
+    def _refresh(self, ps, stream: int) -> None:
+        """After an update: 16-bit parameters take the rounded value of their master weights."""
+        low = [p for p in ps if p in self.master]
+        if not low:
+            return
+        with torch.cuda.stream(torch.cuda.ExternalStream(stream) if self.overlap else torch.cuda.current_stream()):
+            for p in low:
+                p.data.copy_(self.master[p])
 
     # ---- streams ----
     def _launch_stream(self) -> int:
@@ -113,7 +131,10 @@ class _HookedAccumulation:
             raise ValueError("gradients of one layer must share a dtype")
         first = self.fused_edges and self.micro == 0
         last = self.fused_edges and self.micro == self.N - 1
-        self._fold(ps, grads, gdt, first, last, self._launch_stream())
+        stream = self._launch_stream()
+        self._fold(ps, grads, gdt, first, last, stream)
+        if last:
+            self._refresh(ps, stream)
         if self.overlap:
             for g in grads:                            # the side stream still reads them
                 g.record_stream(self._side)
@@ -133,7 +154,9 @@ class _HookedAccumulation:
         if self.micro != self.N:
             raise RuntimeError(f"step() after {self.micro} of {self.N} micro-batches")
         if not self.fused_edges:
-            self._apply_all(self._launch_stream())
+            stream = self._launch_stream()
+            self._apply_all(stream)
+            self._refresh([p for ps in self.layers for p in ps], stream)
         if self.overlap and self._side is not None:
             torch.cuda.current_stream().wait_stream(self._side)
 
@@ -163,11 +186,12 @@ class AdamAccumulation(_HookedAccumulation):
         self.m, self.v = {}, {}
         super().__init__(layers, N, fused_edges, weight_decay, grad_scale, overlap)
         self._state_list = binding.state_list(
-            [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel()) for ps in self.layers for p in ps])
+            [(self._theta(p).data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), p.numel())
+             for ps in self.layers for p in ps])
 
     def _alloc_state(self, p) -> None:
-        self.m[p] = torch.zeros_like(p)
-        self.v[p] = torch.zeros_like(p)
+        self.m[p] = torch.zeros_like(p, dtype=torch.float32)
+        self.v[p] = torch.zeros_like(p, dtype=torch.float32)
 
     def _decay_all(self, stream: int) -> None:
         binding.adama_begin_step_multi(self._state_list, None, self.beta1, self.beta2, stream)
@@ -175,7 +199,7 @@ class AdamAccumulation(_HookedAccumulation):
     def _fold(self, ps, grads, gdt, first: bool, last: bool, stream: int) -> None:
         if last:
             binding.adama_fold_last_apply_opt_multi(
-                [(p.data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel())
+                [(self._theta(p).data_ptr(), self.m[p].data_ptr(), self.v[p].data_ptr(), g.data_ptr(), p.numel())
                  for p, g in zip(ps, grads)], None, gdt, self.N, self.lr, self.eps, self.beta1, self.beta2, self.t,
                 self._opt, stream)
             return
@@ -201,16 +225,16 @@ class MomentumAccumulation(_HookedAccumulation):
         self.b = {}
         super().__init__(layers, N, fused_edges, weight_decay, grad_scale, overlap)
         self._state_list = binding.sgdm_list(
-            [(p.data_ptr(), self.b[p].data_ptr(), None, p.numel()) for ps in self.layers for p in ps])
+            [(self._theta(p).data_ptr(), self.b[p].data_ptr(), None, p.numel()) for ps in self.layers for p in ps])
 
     def _alloc_state(self, p) -> None:
-        self.b[p] = torch.zeros_like(p)
+        self.b[p] = torch.zeros_like(p, dtype=torch.float32)
 
     def _decay_all(self, stream: int) -> None:
         binding.adama_sgdm_begin_step_multi(self._state_list, None, self.momentum, stream)
 
     def _fold(self, ps, grads, gdt, first: bool, last: bool, stream: int) -> None:
-        entries = [(p.data_ptr(), self.b[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
+        entries = [(self._theta(p).data_ptr(), self.b[p].data_ptr(), g.data_ptr(), p.numel()) for p, g in zip(ps, grads)]
         if last:
             binding.adama_sgdm_fold_last_apply_multi(entries, None, gdt, self.N, self.lr, self._opt, stream)
         elif first:

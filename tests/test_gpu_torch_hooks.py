@@ -276,3 +276,49 @@ def test_side_stream_folds_give_the_same_bits():
                 opt.remove_hooks()
             for a, b in zip(*results):
                 assert torch.equal(a, b), f"{cls.__name__} fused={fused}: side-stream result differs"
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_hooks_with_bfloat16_parameters_and_float32_master_weights(fused):
+    """A bfloat16 model: autograd produces bfloat16 gradients, the optimizer keeps float32 master
+    weights, m and v; after the mini-batch the master weights match the oracle fed with the very
+    gradient bits, and every parameter is the rounded value of its master weight."""
+    import torch
+
+    from paper_2305_19982_amd.torch_hooks import AdamAccumulation, leaf_layers
+
+    N, lr, b1, b2, eps = 3, 1e-3, 0.9, 0.999, 1e-8
+    ref_model = _model(torch).bfloat16()
+    model = copy.deepcopy(ref_model)
+    data = [(x.bfloat16(), y.bfloat16()) for (x, y) in _batches(torch, N, 1)[0]]
+    loss_fn = torch.nn.MSELoss()
+    layers = leaf_layers(model)
+    opt = AdamAccumulation(layers, lr=lr, betas=(b1, b2), eps=eps, N=N, fused_edges=fused)
+    params = [p for ps in layers for p in ps]
+    ref_params = list(ref_model.parameters())
+    assert all(p in opt.master and opt.master[p].dtype == torch.float32 for p in params)
+    ref = oracle.OracleState([p.detach().float().cpu().numpy() for p in params])
+    theta0 = [x.copy() for x in ref.theta]
+    ref.begin_step(b1, b2)
+    opt.begin_mini_batch()
+    for (x, y) in data:
+        ref_model.zero_grad(set_to_none=True)
+        loss_fn(ref_model(x), y).backward()
+        for i, rp in enumerate(ref_params):
+            assert rp.grad.dtype == torch.bfloat16
+            bits = rp.grad.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16).ravel()
+            ref.fold(i, bits, N, b1, b2, gdtype="bf16")
+        loss_fn(model(x), y).backward()
+        opt.micro_batch_done()
+        assert all(p.grad is None for p in params)
+    opt.step()
+    ref.apply(lr, eps, b1, b2)
+    torch.cuda.synchronize()
+    for i, p in enumerate(params):
+        name = f"bf16 hooks fused={fused} param {i}"
+        check_close(name, "m", opt.m[p].cpu().numpy().ravel(), ref.m[i])
+        check_close(name, "v", opt.v[p].cpu().numpy().ravel(), ref.v[i])
+        master = opt.master[p]
+        check_close(name, "theta", master.cpu().numpy().ravel(), ref.theta[i], theta0[i].astype(np.float32), theta0[i])
+        assert torch.equal(p.detach(), master.bfloat16()), f"{name}: parameter is not the rounded master weight"
+    opt.remove_hooks()
