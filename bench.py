@@ -156,6 +156,80 @@ def cpu_baseline_all_cores(w, budget_s: float = 8.0, optimizer: str = "adama") -
                       f"oracle, {spent:.1f} s, fp64"}
 
 
+def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_elems: int = 1_557_611_200) -> dict:
+    """What the memory system delivers for the access mixes of the path's kernels, without their arithmetic
+    (synth_stream_probe_kernel): pure read, pure write, and the read : write mixes of fold, decay, update and
+    rescale, as sustained launches of one transformer block's size marching through arrays as large as the
+    GPT-2-1.5B-shaped state; then the fold mix over a sweep of launch sizes, fitted as t = a + n / b."""
+    import numpy as np
+    import torch
+
+    import synth
+    from synth import gen
+
+    dev = "cuda:0"
+    stream = torch.cuda.Stream(device=dev)
+    with torch.cuda.stream(stream):
+        arrays = [torch.zeros(arena_elems, dtype=torch.float32, device=dev) for _ in range(3)]
+        g = torch.zeros(arena_elems, dtype=torch.float32, device=dev)      # read as 16-bit or as float32 elements
+        sink = torch.zeros(4, dtype=torch.float32, device=dev)
+    stream.synchronize()
+    sh = stream.cuda_stream
+
+    def sustained(mode: str, block: int, n: int, passes: int = 2) -> tuple:
+        n -= n % (block * 4)
+        slots = max(1, arena_elems // n)
+
+        def launch(r: int) -> None:
+            off = (r % slots) * n
+            gen.stream_probe(mode, block, g.data_ptr() + 4 * off, arrays[0].data_ptr() + 4 * off,
+                             arrays[1].data_ptr() + 4 * off, arrays[2].data_ptr() + 4 * off, sink.data_ptr(), n, sh)
+
+        reps = max(passes * slots, 20)
+        for r in range(min(slots, reps)):
+            launch(r)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for r in range(reps):
+            launch(r)
+        e1.record(stream)
+        e1.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        return n, us, gen.stream_probe_bytes(mode) * n / (us * 1e-6) / 1e9
+
+    out = {"launch_elems": launch_elems, "array_elems": arena_elems, "modes": {}, "note":
+           "one workgroup per block*4 elements, 16-byte accesses, all non-temporal, no optimizer arithmetic; "
+           "GB/s = bytes the mode moves / HIP-event time over back-to-back launches"}
+    for rnd in range(2):                       # two rounds, the better one is kept (first-touch effects)
+        for mode in gen.PROBE_MODES:
+            for block in block_sizes:
+                n, us, gbs = sustained(mode, block, launch_elems)
+                key = f"{mode}/{block}"
+                if key not in out["modes"] or gbs > out["modes"][key]["GB/s"]:
+                    out["modes"][key] = {"bytes_per_element": gen.stream_probe_bytes(mode), "us_per_launch": round(us, 2),
+                                         "GB/s": round(gbs, 1)}
+    best = {m: max(out["modes"][f"{m}/{b}"]["GB/s"] for b in block_sizes) for m in gen.PROBE_MODES}
+    rd, wr = best["read_g16_m_v"], best["write_m_v"]
+    out["best"] = best
+    # time on the memory bus adds up: a mix of r read bytes and w written bytes cannot beat (r + w) / (r / R + w / W)
+    out["harmonic_ceiling"] = {name: round((r + w) / (r / rd + w / wr), 1)
+                               for name, (r, w) in {"fold_mix_g16": (10, 8), "fold_mix_g32": (12, 8), "decay_mix": (8, 8),
+                                                    "update_mix": (12, 4), "rescale_mix": (12, 12)}.items()}
+    sweep = []
+    for n in (1 << 20, 1 << 22, 1 << 23, 1 << 24, launch_elems, 1 << 26, 1 << 27, 1 << 28):
+        n_, us, gbs = sustained("fold_mix_g16", 128, n)
+        sweep.append({"elems": n_, "us_per_launch": round(us, 2), "GB/s": round(gbs, 1)})
+    xs = np.array([p["elems"] * 18.0 for p in sweep])
+    ts = np.array([p["us_per_launch"] for p in sweep])
+    slope, icpt = np.polyfit(xs, ts, 1)
+    out["launch_size_sweep"] = {"mode": "fold_mix_g16/128", "points": sweep,
+                                "fit": {"fixed_us_per_launch": round(float(icpt), 2),
+                                        "asymptotic_GB/s": round(1.0 / slope / 1e3, 1)}}
+    del synth
+    return out
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -169,6 +243,9 @@ def main() -> int:
     ap.add_argument("--graph", action="store_true",
                     help="also time one micro-batch's fold sweep as eager launches and as a HIP graph replay")
     ap.add_argument("--cpu-budget", type=float, default=15.0, help="seconds of oracle time for cpu_baseline (0 = skip)")
+    ap.add_argument("--stream-probe", action="store_true",
+                    help="instead of the benchmark: measure what the memory system delivers for the read : write mixes "
+                         "of the path's kernels (no optimizer arithmetic) and print that as one JSON line")
     ap.add_argument("--no-torch-ops", action="store_true",
                     help="skip the context figure for the same fold written as stock PyTorch tensor ops")
     args = ap.parse_args()
@@ -187,7 +264,10 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
-    binding.load()                      # fails loudly if libadama.so is missing
+    if args.stream_probe:
+        print(json.dumps({"stream_probe": stream_probe(), "peak_GB/s": HBM_PEAK_GBS}), flush=True)
+        return 0
+    binding.load()                      # raises if libadama.so is missing or older than its sources
     w = configs.FULL[args.workload]()
     opt = args.optimizer
     hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model",

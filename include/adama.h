@@ -244,6 +244,11 @@ adama_status adama_sgdm_fold_last_apply_multi(const adama_sgdm_tensor *list, int
  * on the same thread. */
 const char *adama_last_error(void);
 
+/* Host-only: 16 hexadecimal digits identifying the sources and compiler flags the loaded library was
+ * built from (a hash the build script passes in), "unidentified" for a build without one.  Lets a
+ * caller refuse a binary that does not match the sources beside it.  Static storage. */
+const char *adama_build_id(void);
+
 /* Number of tensors one launch's descriptor table holds. */
 #define ADAMA_MAX_TENSORS_PER_LAUNCH 80
 int adama_max_tensors_per_launch(void);

@@ -59,12 +59,29 @@ def library_path() -> str:
     return _build.LIB
 
 
+def _may_build_here() -> bool:
+    """A build spawns hipcc: not from a process that has already initialised the GPU, nor under a profiler
+    (whose preloaded tool library the compiler processes would inherit)."""
+    import sys
+
+    torch = sys.modules.get("torch")
+    if torch is not None and torch.cuda.is_initialized():
+        return False
+    return not any("rocprof" in os.environ.get(k, "").lower() for k in ("LD_PRELOAD", "ROCP_TOOL_LIBRARIES"))
+
+
 def load() -> ctypes.CDLL:
-    """Load libadama.so (building it first only if it does not exist at all)."""
+    """Load libadama.so.  A library that is missing, or that was built from other sources than the present
+    ones (build.stale()), is rebuilt first where that is safe and refused with an error otherwise: a
+    stale binary is never used silently."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _build.stale():
+        if not _may_build_here():
+            raise RuntimeError(f"{_build.LIB} is missing or was built from other sources (library "
+                               f"{_build.library_id()}, sources {_build.source_id()}); build it first: "
+                               "python -c 'import __graft_entry__ as g; g.build()'")
         _build.build_libadama()
     lib = ctypes.CDLL(_build.LIB)
     vp, sz, dbl, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_double, ctypes.c_int, ctypes.c_longlong
@@ -112,6 +129,8 @@ def load() -> ctypes.CDLL:
     lib.adama_last_error.argtypes = []
     lib.adama_max_tensors_per_launch.restype = i32
     lib.adama_max_tensors_per_launch.argtypes = []
+    lib.adama_build_id.restype = ctypes.c_char_p
+    lib.adama_build_id.argtypes = []
     lib.adama_launch_chunk.restype = i32
     lib.adama_launch_chunk.argtypes = [i32, ctypes.c_ulonglong]
     lib.adama_tuning.restype = None
@@ -136,6 +155,10 @@ def _check(status: int) -> None:
 
 def adama_last_error() -> str:
     return load().adama_last_error().decode("utf-8", "replace")
+
+
+def adama_build_id() -> str:
+    return load().adama_build_id().decode()
 
 
 def adama_max_tensors_per_launch() -> int:

@@ -1,6 +1,7 @@
 """Builds libadama.so for gfx950 with hipcc, in-tree (next to this file)."""
 from __future__ import annotations
 
+import hashlib
 import os
 import subprocess
 
@@ -19,17 +20,41 @@ HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-ffp-contract=off"
                "-Wall", "-Wno-unused-command-line-argument", "-fPIC", "-shared"]
 
 
+_ID_MARKER = b"ADAMA_BUILD_ID="
+
+
+def source_id() -> str:
+    """Identifies what a library is built from: the compiler flags and the bytes of every source and header."""
+    h = hashlib.sha256(" ".join(HIPCC_FLAGS).encode())
+    for p in SOURCES + HEADERS:
+        with open(p, "rb") as fh:
+            h.update(b"\0" + os.path.basename(p).encode() + b"\0" + fh.read())
+    return h.hexdigest()[:16]
+
+
+def library_id(path: str = LIB) -> str | None:
+    """The source_id() a built library carries (the string adama_build_id() returns), read from the file
+    without loading it; None if the file is missing or carries none."""
+    if not os.path.exists(path):
+        return None
+    with open(path, "rb") as fh:
+        blob = fh.read()
+    at = blob.find(_ID_MARKER)
+    if at < 0:
+        return None
+    return blob[at + len(_ID_MARKER): at + len(_ID_MARKER) + 16].decode("ascii", "replace")
+
+
 def stale() -> bool:
-    if not os.path.exists(LIB):
-        return True
-    built = os.path.getmtime(LIB)
-    return any(os.path.getmtime(p) > built for p in SOURCES + HEADERS)
+    """True when libadama.so is missing or was built from sources (or flags) other than the present ones.
+    Compares contents, not file times, so a copied or checked-out tree is judged correctly."""
+    return library_id() != source_id()
 
 
 def build_libadama(verbose: bool = False) -> str:
     tmp = LIB + f".tmp{os.getpid()}"
-    cmd = ["hipcc", *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", os.path.join(PKG, "csrc"),
-           "-o", tmp, *SOURCES]
+    cmd = ["hipcc", *HIPCC_FLAGS, f'-DADAMA_BUILD_ID="{source_id()}"', "-I", os.path.join(ROOT, "include"),
+           "-I", os.path.join(PKG, "csrc"), "-o", tmp, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)

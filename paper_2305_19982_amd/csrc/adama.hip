@@ -23,6 +23,13 @@ namespace {
 
 thread_local char g_error[512] = "";
 
+// Identifies the sources and flags this library was built from (the build script passes a hash of
+// them); the marker in front lets a build script find it in the file without loading the library.
+#ifndef ADAMA_BUILD_ID
+#define ADAMA_BUILD_ID "unidentified"
+#endif
+const char kBuildId[] = "ADAMA_BUILD_ID=" ADAMA_BUILD_ID;
+
 adama_status fail(adama_status st, const char *fmt, ...)
 {
     va_list ap;
@@ -383,6 +390,8 @@ extern "C" {
 const char *adama_last_error(void) { return g_error; }
 
 int adama_max_tensors_per_launch(void) { return kMaxTensors; }
+
+const char *adama_build_id(void) { return kBuildId + sizeof("ADAMA_BUILD_ID=") - 1; }
 
 int adama_launch_chunk(int op, unsigned long long launch_elems)
 {

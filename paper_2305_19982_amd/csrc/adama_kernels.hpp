@@ -140,12 +140,15 @@ template <> struct Grad<kF16> {    // hardware conversion; exact, subnormals inc
 //                            bit for bit.
 //   SGD with momentum:       b <- mu*b;  b <- b + c1*g;  theta <- theta - (lr*lambda*theta + lr*b)
 // x * (hi + lo) with one rounding at x's magnitude: the small product is rounded first, the fused
-// multiply-add rounds the sum.  With lo == 0 (a factor float32 holds exactly) this is hi * x, also for
-// an infinite x.
+// multiply-add rounds the sum.  With lo == 0 (a factor float32 holds exactly) this is hi * x.  An
+// infinite x also takes hi * x: lo may be negative (float32(0.999) is above 0.999), and then
+// hi * inf + lo * inf would be inf - inf = NaN where the product x * (hi + lo) is plainly infinite.
+// (A NaN stays a NaN on either route.)
 __device__ __forceinline__ float scale_hi_lo(float hi, float lo, float x)
 {
     const float whole = __builtin_fmaf(hi, x, lo * x);
-    return lo != 0.0f ? whole : hi * x;
+    const bool split = lo != 0.0f && __builtin_fabsf(x) < __builtin_inff();
+    return split ? whole : hi * x;
 }
 
 template <int OpK>

@@ -124,7 +124,30 @@ def _device_lib():
                                               ctypes.POINTER(_Spec), ctypes.c_void_p]
         _device.synth_copy_device.restype = ctypes.c_int
         _device.synth_copy_device.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_void_p]
+        _device.synth_stream_probe.restype = ctypes.c_int
+        _device.synth_stream_probe.argtypes = [ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 5 + [ctypes.c_uint64,
+                                                                                                    ctypes.c_void_p]
+        _device.synth_stream_probe_bytes.restype = ctypes.c_int
+        _device.synth_stream_probe_bytes.argtypes = [ctypes.c_int]
     return _device
+
+
+# Traffic-mix probe (synth_device.hip): streams with the access mix of the optimizer's kernels, no arithmetic.
+PROBE_MODES = {"read_g16_m_v": 0, "write_m_v": 1, "fold_mix_g16": 2, "fold_mix_g32": 3, "decay_mix": 4,
+               "update_mix": 5, "rescale_mix": 6, "read_3xf32": 7}
+
+
+def stream_probe_bytes(mode: str) -> int:
+    return int(_device_lib().synth_stream_probe_bytes(PROBE_MODES[mode]))
+
+
+def stream_probe(mode: str, block: int, g: int, a0: int, a1: int, a2: int, sink: int, n: int, stream: int) -> None:
+    """Enqueue one probe launch over n elements (a multiple of block*4) of device arrays at the given addresses."""
+    rc = _device_lib().synth_stream_probe(PROBE_MODES[mode], block, ctypes.c_void_p(g), ctypes.c_void_p(a0),
+                                          ctypes.c_void_p(a1), ctypes.c_void_p(a2), ctypes.c_void_p(sink), n,
+                                          ctypes.c_void_p(stream))
+    if rc:
+        raise RuntimeError(f"synth_stream_probe({mode}, block={block}, n={n}) failed ({rc})")
 
 
 def copy_device(dst: int, src: int, nbytes: int, stream: int) -> None:

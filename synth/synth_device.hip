@@ -44,3 +44,85 @@ extern "C" int synth_copy_device(void *dst, const void *src, uint64_t bytes, voi
                        (synth_f32x4 *)dst, (const synth_f32x4 *)src, bytes / 16);
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
+
+/* ---- traffic-mix probe ----
+   Streams with the access mix of the optimizer's kernels and none of its arithmetic, to measure what
+   the memory system delivers for a given read : write ratio: one workgroup of BLOCK threads per chunk
+   of BLOCK*4 elements, one 16-byte access per lane per float32 array (8-byte for the 16-bit array),
+   every access non-temporal.  A mode is described by which arrays are read and which are written:
+     g16 : a 2-byte-per-element array, read only          (a bf16 / fp16 gradient)
+     g32 : a 4-byte-per-element array, read only          (an fp32 gradient, or a moment the update only reads)
+     rw  : number of float32 arrays read and written back (moments, parameters)
+     ro  : number of further float32 arrays read only
+     wo  : number of float32 arrays written only
+   Arrays are taken from a0, a1, a2 in the order rw, ro, wo. */
+typedef uint32_t synth_u32x2 __attribute__((ext_vector_type(2)));
+#define SYNTH_GLOBAL __attribute__((address_space(1)))
+
+template <int BLOCK, int G16, int G32, int RW, int RO, int WO>
+__global__ void __launch_bounds__(BLOCK) synth_stream_probe_kernel(const void *g, float *a0, float *a1, float *a2, float *sink)
+{
+    static_assert(RW + RO + WO <= 3, "three float32 arrays at most");
+    const uint64_t e0 = (uint64_t)blockIdx.x * (BLOCK * 4);
+    const uint32_t i = threadIdx.x;
+    float *arr[3] = {a0, a1, a2};
+    synth_f32x4 x[3];
+    synth_f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (G16) {
+        synth_u32x2 w = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_u32x2 *)((const uint16_t *)g + e0) + i);
+        acc.x += __builtin_bit_cast(float, w.x << 16);
+        acc.y += __builtin_bit_cast(float, w.y << 16);
+    }
+    if (G32) acc += __builtin_nontemporal_load((const SYNTH_GLOBAL synth_f32x4 *)((const float *)g + e0) + i);
+#pragma unroll
+    for (int k = 0; k < RW + RO; ++k) x[k] = __builtin_nontemporal_load((SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+#pragma unroll
+    for (int k = RW; k < RW + RO; ++k) acc += x[k];
+#pragma unroll
+    for (int k = 0; k < RW; ++k) __builtin_nontemporal_store(x[k] + acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+#pragma unroll
+    for (int k = RW + RO; k < RW + RO + WO; ++k) __builtin_nontemporal_store(acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+    if (RW + WO == 0 && acc.x + acc.y + acc.z + acc.w == 12345.678f) *sink = acc.x;   /* keeps read-only loads alive */
+}
+
+template <int BLOCK>
+static void synth_stream_probe_launch(int mode, unsigned grid, const void *g, float *a0, float *a1, float *a2, float *sink, hipStream_t s)
+{
+#define SYNTH_PROBE(G16, G32, RW, RO, WO) \
+    hipLaunchKernelGGL((synth_stream_probe_kernel<BLOCK, G16, G32, RW, RO, WO>), dim3(grid), dim3(BLOCK), 0, s, g, a0, a1, a2, sink)
+    switch (mode) {
+    case 0: SYNTH_PROBE(1, 0, 0, 2, 0); break;   /* read only, fold's inputs: g16, m, v         10 B/element */
+    case 1: SYNTH_PROBE(0, 0, 0, 0, 2); break;   /* write only, fold's outputs: m, v             8 */
+    case 2: SYNTH_PROBE(1, 0, 2, 0, 0); break;   /* fold mix, 16-bit gradient: r g,m,v  w m,v   18 */
+    case 3: SYNTH_PROBE(0, 1, 2, 0, 0); break;   /* fold mix, fp32 gradient                     20 */
+    case 4: SYNTH_PROBE(0, 0, 2, 0, 0); break;   /* decay mix: r m,v  w m,v                     16 */
+    case 5: SYNTH_PROBE(0, 0, 1, 2, 0); break;   /* update mix: r theta,m,v  w theta            16 */
+    case 6: SYNTH_PROBE(0, 0, 3, 0, 0); break;   /* rescale mix: r and w theta,m,v              24 */
+    case 7: SYNTH_PROBE(0, 0, 0, 3, 0); break;   /* read only, three fp32 arrays                12 */
+    default: break;
+    }
+#undef SYNTH_PROBE
+}
+
+/* Bytes per element of a probe mode, 0 for an unknown mode. */
+extern "C" int synth_stream_probe_bytes(int mode)
+{
+    static const int bytes[8] = {10, 8, 18, 20, 16, 16, 24, 12};
+    return mode >= 0 && mode < 8 ? bytes[mode] : 0;
+}
+
+/* Enqueue one probe launch over the first n elements (n a multiple of block*4, block 128 or 256; arrays
+   16-byte aligned device memory of at least n elements each; g may be NULL for modes without one). */
+extern "C" int synth_stream_probe(int mode, int block, const void *g, float *a0, float *a1, float *a2, float *sink,
+                                  uint64_t n, void *stream)
+{
+    if (n == 0) return 0;
+    if (mode < 0 || mode > 7 || (block != 128 && block != 256) || n % (uint64_t)(block * 4) || !a0 || !a1 || !a2 || !sink)
+        return 1;
+    if ((mode == 0 || mode == 2 || mode == 3) && !g) return 1;
+    if ((((uintptr_t)g | (uintptr_t)a0 | (uintptr_t)a1 | (uintptr_t)a2) & 15) || n / (uint64_t)(block * 4) > 0x7FFFFFFFull) return 1;
+    const unsigned grid = (unsigned)(n / (uint64_t)(block * 4));
+    if (block == 128) synth_stream_probe_launch<128>(mode, grid, g, a0, a1, a2, sink, (hipStream_t)stream);
+    else synth_stream_probe_launch<256>(mode, grid, g, a0, a1, a2, sink, (hipStream_t)stream);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}

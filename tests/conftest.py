@@ -10,6 +10,12 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run on the GPU box only)")
+    # Before anything touches a GPU: a library that is missing or was built from other sources than the
+    # present ones is rebuilt here, so no test ever runs against a stale binary.
+    from paper_2305_19982_amd import build
+
+    if build.stale():
+        build.build_libadama()
 
 
 def pytest_collection_modifyitems(config, items):

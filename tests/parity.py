@@ -16,6 +16,9 @@ scale-aware criteria derived from the arithmetic are gated as well:
 """
 from __future__ import annotations
 
+import os
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 
 import oracle
@@ -23,7 +26,16 @@ import synth
 from synth import configs
 
 RTOL, ATOL = 1e-5, 1e-6
-SLICE = 4096
+# Sampling of full-size workloads: every tensor of at most FULL_BELOW elements is compared in full; a
+# longer one on its first and last SLICE elements plus BLOCKS random SLICE-element blocks.
+FULL_BELOW = 1 << 20
+SLICE = 65536
+BLOCKS = 16
+
+
+def host_threads() -> int:
+    """Threads for the oracle side of a sampled full-size run: the GPU machine grants 16 cores per GPU."""
+    return max(1, min(16, len(os.sched_getaffinity(0))))
 
 
 def check_close(name: str, kind: str, gpu: np.ndarray, ref: np.ndarray, prev_gpu=None, prev_ref=None) -> dict:
@@ -61,10 +73,11 @@ def check_close(name: str, kind: str, gpu: np.ndarray, ref: np.ndarray, prev_gpu
     return stats
 
 
-def slices_of(n: int, rng: np.random.Generator, full_below: int = 65536, blocks: int = 4) -> list:
-    """Element ranges compared for a tensor of n elements: everything if small, else the first and last
-    SLICE elements plus `blocks` random SLICE-element blocks (starts deliberately not aligned)."""
-    if n <= full_below:
+def slices_of(n: int, rng: np.random.Generator, full_below: int = FULL_BELOW, blocks: int = BLOCKS) -> list:
+    """Element ranges compared for a tensor of n elements: everything if it has at most `full_below`
+    elements (or if the sample would cover most of it anyway), else the first and last SLICE elements
+    plus `blocks` random SLICE-element blocks (starts deliberately not aligned; blocks may overlap)."""
+    if n <= full_below or n <= 2 * (blocks + 2) * SLICE:
         return [(0, n)]
     out = [(0, SLICE), (n - SLICE, n)]
     for _ in range(blocks):
@@ -78,7 +91,7 @@ class WorkloadRun:
 
     def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0",
                  fused: bool = False, optimizer: str = "adam", momentum: float = 0.9, weight_decay: float = 0.0,
-                 grad_scale: float = 1.0):
+                 grad_scale: float = 1.0, shadow: bool = False):
         from paper_2305_19982_amd.harness import SimulatedBackward
 
         self.w = w
@@ -92,14 +105,28 @@ class WorkloadRun:
                                     grad_scale=grad_scale)
         rng = np.random.default_rng(1234)
         self.slices = [slices_of(t.n, rng) if sampled else [(0, t.n)] for t in w.tensors]
+        # The oracle is called as it stands; a sampled full-size run merely calls it from several host
+        # threads at once, each on its own compared range (ranges are independent: the method is elementwise).
+        self.pool = ThreadPoolExecutor(max_workers=host_threads()) if sampled else None
         # theta0: the device writes it, the host regenerates the same bits for the oracle
-        theta0 = []
         for t in w.tensors:
             synth.fill_device(self.hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, self.hb.stream_handle)
-            for (a, b) in self.slices[t.index]:
-                theta0.append(synth.fill_host(w.theta_spec(t.index), "f32", b - a, first=a))
         self.key = [(t.index, a, b) for t in w.tensors for (a, b) in self.slices[t.index]]
+        theta0 = self._map(lambda k: synth.fill_host(w.theta_spec(k[0]), "f32", k[2] - k[1], first=k[1]), self.key)
         self.ref = oracle.OracleState(theta0)
+        # Shadow state: a second set of theta, m, v arenas driven through a different launch geometry
+        # (every fold as a single-tensor launch, decay and update as ONE flat launch over the whole
+        # arena, padding included).  The two must end bit-identical over every element of the arenas,
+        # which proves on the full-size workload that no chunk of any list launch was skipped,
+        # repeated or misplaced.  (Adam, separate calls only.)
+        self.shadow = None
+        if shadow:
+            assert optimizer == "adam" and not fused and weight_decay == 0.0 and grad_scale == 1.0
+            import torch
+
+            with torch.cuda.stream(self.hb.stream):
+                self.shadow = {"theta": self.hb.theta.clone(), "m": torch.zeros_like(self.hb.m),
+                               "v": torch.zeros_like(self.hb.v)}
         self.rows = {}
         for r, (ti, a, b) in enumerate(self.key):
             self.rows.setdefault(ti, []).append((r, a, b))
@@ -107,6 +134,16 @@ class WorkloadRun:
         for r in range(len(self.key)):
             assert np.array_equal(self.prev_gpu_theta[r].astype(np.float64), self.ref.theta[r]), \
                 "device and host generators disagree on theta0"
+
+    def close(self) -> None:
+        if self.pool is not None:
+            self.pool.shutdown()
+            self.pool = None
+
+    def _map(self, fn, items) -> list:
+        if self.pool is None:
+            return [fn(x) for x in items]
+        return list(self.pool.map(fn, items))
 
     def download(self, which: str, r: int) -> np.ndarray:
         ti, a, b = self.key[r]
@@ -122,16 +159,39 @@ class WorkloadRun:
     def oracle_fold_layer(self, step: int, micro: int, li: int) -> None:
         w = self.w
         gd = None if w.gdtype == "f32" else w.gdtype
+
+        def one(job) -> None:
+            ti, r, a, b = job
+            g = synth.fill_host(w.grad_spec(step, micro, ti), w.gdtype, b - a, first=a)
+            if self.optimizer == "sgdm":
+                oracle.sgdm_fold(self.ref.m[r], g, w.N, self.grad_scale, gdtype=gd)
+            elif self.grad_scale != 1.0:
+                oracle.fold_scaled(self.ref.m[r], self.ref.v[r], g, w.N, w.beta1, w.beta2, self.grad_scale, gdtype=gd)
+            else:
+                self.ref.fold(r, g, w.N, w.beta1, w.beta2, gdtype=gd)
+
+        self._map(one, [(ti, r, a, b) for ti in w.layers[li] for (r, a, b) in self.rows[ti]])
+
+    # ---- the shadow geometry (see __init__) ----
+    def shadow_fold_layer(self, li: int) -> None:
+        from paper_2305_19982_amd import binding
+
+        w, hb, sh = self.w, self.hb, self.shadow
         for ti in w.layers[li]:
-            spec = w.grad_spec(step, micro, ti)
-            for (r, a, b) in self.rows[ti]:
-                g = synth.fill_host(spec, w.gdtype, b - a, first=a)
-                if self.optimizer == "sgdm":
-                    oracle.sgdm_fold(self.ref.m[r], g, w.N, self.grad_scale, gdtype=gd)
-                elif self.grad_scale != 1.0:
-                    oracle.fold_scaled(self.ref.m[r], self.ref.v[r], g, w.N, w.beta1, w.beta2, self.grad_scale, gdtype=gd)
-                else:
-                    self.ref.fold(r, g, w.N, w.beta1, w.beta2, gdtype=gd)
+            o, n = 4 * hb.offset[ti], w.tensors[ti].n
+            binding.adama_fold(sh["m"].data_ptr() + o, sh["v"].data_ptr() + o, hb.grad_ptr(ti), w.gdtype, n, w.N,
+                               w.beta1, w.beta2, hb.stream_handle)
+
+    def assert_shadow_identical(self) -> int:
+        """Bitwise equality of the whole arenas (padding included); returns the number of elements compared."""
+        import torch
+
+        self.hb.synchronize()
+        for which in ("theta", "m", "v"):
+            a, b = getattr(self.hb, which), self.shadow[which]
+            assert torch.equal(a.view(torch.int32), b.view(torch.int32)), \
+                f"{self.w.name}: {which} differs between the list launches and the flat / single-tensor launches"
+        return 3 * self.hb.arena_elems
 
     def run_step(self, step: int, check_grad_bits: bool = False) -> dict:
         w = self.w
@@ -140,6 +200,11 @@ class WorkloadRun:
             self.hb.begin_step_fused()
         else:
             self.hb.begin_step(w.beta1, w.beta2)
+        if self.shadow is not None:
+            from paper_2305_19982_amd import binding
+
+            binding.adama_begin_step(self.shadow["m"], self.shadow["v"], self.hb.arena_elems, w.beta1, w.beta2,
+                                     self.hb.stream_handle)
         self.oracle_begin_step()
         for i in range(w.N):
             for li in w.backward_layers():
@@ -152,31 +217,39 @@ class WorkloadRun:
                     self.hb.fold_layer_first(li, w.N, w.beta1, w.beta2)
                 else:
                     self.hb.fold_layer(li, w.N, w.beta1, w.beta2)
+                if self.shadow is not None:
+                    self.shadow_fold_layer(li)
                 self.oracle_fold_layer(step, i, li)
         if not self.fused:
             self.hb.apply(w.lr, w.eps, w.beta1, w.beta2)
+        if self.shadow is not None:
+            binding.adama_apply(self.shadow["theta"], self.shadow["m"], self.shadow["v"], self.hb.arena_elems, w.lr,
+                                w.eps, w.beta1, w.beta2, self.hb.t, self.hb.stream_handle)
         self.oracle_apply()
         assert self.hb.t == self.ref.t == step
         return self.compare()
 
     def oracle_begin_step(self) -> None:
         w = self.w
+        self.ref.t += 1
         if self.optimizer == "sgdm":
-            self.ref.t += 1
-            for b in self.ref.m:
-                oracle.sgdm_begin_step(b, self.momentum)
+            self._map(lambda b: oracle.sgdm_begin_step(b, self.momentum), self.ref.m)
         else:
-            self.ref.begin_step(w.beta1, w.beta2)
+            self._map(lambda mv: oracle.begin_step(mv[0], mv[1], w.beta1, w.beta2), list(zip(self.ref.m, self.ref.v)))
 
     def oracle_apply(self) -> None:
         w = self.w
-        for th, m, v in zip(self.ref.theta, self.ref.m, self.ref.v):
+
+        def one(tmv) -> None:
+            th, m, v = tmv
             if self.optimizer == "sgdm":
                 oracle.sgdm_apply(th, m, w.lr, self.weight_decay)
             elif self.weight_decay != 0.0:
                 oracle.apply_adamw(th, m, v, w.lr, w.eps, w.beta1, w.beta2, self.ref.t, self.weight_decay)
             else:
                 oracle.apply(th, m, v, w.lr, w.eps, w.beta1, w.beta2, self.ref.t)
+
+        self._map(one, list(zip(self.ref.theta, self.ref.m, self.ref.v)))
 
     def assert_grad_bits(self, step: int, micro: int, li: int) -> None:
         """What the device wrote into the gradient buffer is what the host regenerates for the oracle."""

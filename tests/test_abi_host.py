@@ -39,6 +39,17 @@ def test_header_constants_match_library(lib):
     assert binding.adama_max_tensors_per_launch() == declared
 
 
+def test_loaded_library_matches_the_sources_beside_it(lib):
+    """The build id a library carries is a hash of its sources and flags; the binding refuses (or
+    rebuilds) a binary whose id differs, so an edited kernel is never tested against an old build."""
+    from paper_2305_19982_amd import build
+
+    assert re.fullmatch(r"[0-9a-f]{16}", binding.adama_build_id())
+    assert binding.adama_build_id() == build.library_id() == build.source_id()
+    assert not build.stale()
+    assert build.library_id(os.path.join(ROOT, "include", "adama.h")) is None      # a file without the marker
+
+
 def test_empty_inputs_are_noops(lib):
     binding.adama_begin_step(None, None, 0, 0.9, 0.999)
     binding.adama_fold(None, None, None, "bf16", 0, 4, 0.9, 0.999)

@@ -331,6 +331,7 @@ def test_full_size_c3_variants_sampled(torch_cuda, optimizer):
     run = WorkloadRun(w, pack="aligned", sampled=True, fused=True, **kw)
     stats = run.run_step(1)
     print(f"{w.name} [full size, {optimizer}] step 1: {stats}", flush=True)
+    run.close()
     del run
     import gc
 

@@ -1,9 +1,18 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times (one
 adama_fold_multi launch per layer, backward order, every micro-batch), on sampled element ranges the
-oracle can afford: every tensor of at most 65536 elements in full; for longer tensors the first and
-last 4096 elements plus four random 4096-element blocks.  The host regenerates exactly the bits the
+oracle can afford: every tensor of at most 2^20 elements in full; for longer tensors the first and
+last 65536 elements plus sixteen random 65536-element blocks (about 230 M compared elements of the
+GPT-2-shaped workload, 290 M of the 12.75 B-parameter one).  The host regenerates exactly the bits the
 device generator wrote (checked bit for bit in test_gpu_parity.py), so no data flows from the GPU path
-into the oracle."""
+into the oracle; the oracle is called from 16 host threads, each on its own compared range.
+
+Two whole-arena checks cover what sampling cannot:
+* every second moment of every tensor is positive after the run (a gradient element is never exactly 0
+  in all micro-batches here) and every padding element between tensors is still 0: no chunk skipped,
+  nothing written outside a tensor;
+* where HBM allows (all but the 12.75 B-parameter workload), a shadow copy of the state goes through a
+  different launch geometry (single-tensor folds, flat whole-arena decay and update) and must end
+  bit-identical over all of theta, m and v."""
 import gc
 import time
 
@@ -15,24 +24,42 @@ from synth import configs
 pytestmark = pytest.mark.gpu
 
 
-def _run_full(name):
+def _count_positive(x, piece=1 << 28) -> int:
+    return sum(int((x[a:a + piece] > 0).sum()) for a in range(0, x.numel(), piece))
+
+
+def _run_full(name, shadow=True):
     import torch
 
     w = configs.FULL[name]()
     t0 = time.time()
     print(f"{w.name}: P={w.P} tensors={len(w.tensors)} layers={len(w.layers)} N={w.N} steps={w.steps}", flush=True)
-    run = WorkloadRun(w, pack="aligned", sampled=True)
+    run = WorkloadRun(w, pack="aligned", sampled=True, shadow=shadow)
     sampled = sum(b - a for (_, a, b) in run.key)
-    print(f"  state resident, {len(run.key)} compared ranges, {sampled} elements ({time.time() - t0:.1f} s)", flush=True)
+    print(f"  state resident, {len(run.key)} compared ranges, {sampled} elements = {100.0 * sampled / w.P:.2f} % "
+          f"({time.time() - t0:.1f} s)", flush=True)
     for step in range(1, w.steps + 1):
         stats = run.run_step(step)
         print(f"  step {step} ok after {time.time() - t0:.1f} s: {stats}", flush=True)
+    # whole-arena coverage: v > 0 on every element of every tensor, 0 on the padding between tensors
+    run.hb.synchronize()
+    positive = _count_positive(run.hb.v)
+    zero_prob = w.p_zero ** (w.N * w.steps)          # an element whose every gradient was exactly 0
+    assert positive <= w.P, f"{positive} positive second moments but only {w.P} parameters: a write outside a tensor"
+    assert positive >= w.P * (1.0 - zero_prob) - 64, f"only {positive} of {w.P} second moments are positive: a chunk was skipped"
+    print(f"  coverage: {positive} of {w.P} second moments positive, {run.hb.arena_elems - w.P} padding elements still 0",
+          flush=True)
+    if shadow:
+        n = run.assert_shadow_identical()
+        print(f"  shadow geometry (single-tensor folds, flat decay / update): {n} state elements bit-identical "
+              f"({time.time() - t0:.1f} s)", flush=True)
     peak, whole = run.hb.peak_grad_bytes, run.hb.whole_model_grad_bytes
     print(f"  peak gradient memory {peak} B (largest layer) vs {whole} B for whole-model gradients: 1/{whole / peak:.1f}",
           flush=True)
     assert peak < (w.largest_layer_elems + 128 * 32) * w.grad_bytes
     if len(w.layers) > 2:
         assert peak < whole
+    run.close()
     del run
     gc.collect()
     torch.cuda.empty_cache()
@@ -58,7 +85,7 @@ def test_c5_decoder_10b_full_size():
     free, total = torch.cuda.mem_get_info()
     if free < 170 * (1 << 30):
         pytest.skip(f"needs ~155 GB of free HBM, {free >> 30} GB available")
-    peak, whole = _run_full("c5")
+    peak, whole = _run_full("c5", shadow=False)      # a second copy of 153 GB of state does not fit
     assert peak < whole / 40          # one block (629 MB) vs 25.5 GB
 
 
