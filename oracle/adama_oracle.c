@@ -236,7 +236,10 @@ void adama_oracle_fold_scaled(double *m, double *v, const double *grad, size_t n
 /* parameter directly, scaled by the learning rate, and never enters    */
 /* m or v:                                                              */
 /*   theta <- theta - lr * lambda * theta - lr * m_hat/(sqrt(v_hat)+eps)*/
-/* Both terms use the parameter value from before the step.             */
+/* Both terms use the parameter value from before the step.  lambda = 0 */
+/* is the paper's plain update: there is no decay term then (library    */
+/* optimizers skip it too), so 0 * theta is never formed and an         */
+/* infinite parameter stays infinite instead of turning into NaN.       */
 /* ------------------------------------------------------------------ */
 void adama_oracle_apply_adamw(double *theta, const double *m, const double *v, size_t n,
                               double lr, double eps, double beta1, double beta2, long long t,
@@ -248,6 +251,7 @@ void adama_oracle_apply_adamw(double *theta, const double *m, const double *v, s
         double m_hat = m[k] / bias1;
         double v_hat = v[k] / bias2;
         double decay = lr * weight_decay * theta[k];
+        if (weight_decay == 0.0) decay = 0.0;   /* no decay: the term is absent, also for an infinite theta */
         theta[k] = theta[k] - decay - lr * m_hat / (sqrt(v_hat) + eps);
     }
 }
@@ -282,6 +286,7 @@ void adama_oracle_sgdm_apply(double *theta, const double *b, size_t n, double lr
 {
     for (size_t k = 0; k < n; ++k) {
         double decay = lr * weight_decay * theta[k];
+        if (weight_decay == 0.0) decay = 0.0;   /* no decay: the term is absent, also for an infinite theta */
         theta[k] = theta[k] - decay - lr * b[k];
     }
 }

@@ -563,6 +563,61 @@ def pin_sgdm_closed_forms(lib):
         assert Fraction(float(th[k])) == e, f"SGD apply [{k}]"
 
 
+def pin_non_finite_values(lib):
+    """IEEE special cases worked out by hand (beta > 0, lr > 0): an infinite moment decays to the same
+    infinity; an infinite gradient makes m infinite of its sign and v +inf; the update leaves theta alone
+    when only v is infinite (finite / inf = 0), sends it to -/+inf when only m is +/-inf, and gives NaN
+    for inf / inf; NaN stays NaN.  Momentum SGD with an infinite gradient, two steps, against
+    torch.optim.SGD (which forms no decay term for weight_decay = 0): buffer and parameter keep their
+    infinities.  lambda = 0 reproduces the plain update bit for bit on infinite parameters too."""
+    import torch
+
+    inf, nan = np.inf, np.nan
+    m = np.array([1.0, inf, -inf, nan, 2.0, 0.5])
+    v = np.array([inf, 3.0, inf, 1.0, nan, 0.25])
+    oracle.begin_step(m, v, 0.9, 0.999, lib=lib)
+    assert m[1] == inf and m[2] == -inf and np.isnan(m[3]) and v[0] == inf and v[2] == inf and np.isnan(v[4])
+    assert m[0] == 0.9 and v[5] == 0.999 * 0.25
+    m, v = np.zeros(4), np.zeros(4)
+    for kind in ("f64", "f32", "bf16", "f16"):
+        arr, gdt, _ = encode_grad(np.array([inf, -inf, 1.0, 0.0]), kind)
+        if kind == "f64":
+            arr = np.array([inf, -inf, nan, 0.0])
+        mm, vv = m.copy(), v.copy()
+        oracle.fold(mm, vv, arr, 4, 0.9, 0.999, gdtype=gdt, lib=lib)
+        assert mm[0] == inf and mm[1] == -inf and vv[0] == inf and vv[1] == inf and mm[3] == 0 and vv[3] == 0, kind
+        if kind == "f64":
+            assert np.isnan(mm[2]) and np.isnan(vv[2])
+    theta0 = np.array([1.5, -2.5, 3.5, 4.5, 5.5, inf, -inf])
+    theta = theta0.copy()
+    m = np.array([1e-3, inf, -inf, inf, nan, 1e-3, 1e-3])
+    v = np.array([inf, 1e-6, 1e-6, inf, 1e-6, 1e-6, 1e-6])
+    oracle.apply(theta, m, v, 1e-3, 1e-8, 0.9, 0.999, 2, lib=lib)
+    assert theta[0] == 1.5 and theta[1] == -inf and theta[2] == inf and np.isnan(theta[3]) and np.isnan(theta[4])
+    assert theta[5] == inf and theta[6] == -inf
+    plain = theta.copy()
+    theta = theta0.copy()
+    oracle.apply_adamw(theta, m, v, 1e-3, 1e-8, 0.9, 0.999, 2, 0.0, lib=lib)
+    assert np.array_equal(theta, plain, equal_nan=True), "lambda = 0 must be the plain update, infinite parameters included"
+    # momentum SGD against the library over two steps
+    n, mu, lr = 6, 0.8, 0.05
+    g1 = np.array([inf, -inf, 1.0, -2.0, nan, 0.5])
+    g2 = np.array([1.0, 1.0, 1.0, inf, 1.0, -0.5])
+    th0 = np.linspace(-1.0, 1.0, n)
+    p = torch.nn.Parameter(torch.from_numpy(th0.copy()))
+    opt = torch.optim.SGD([p], lr=lr, momentum=mu, dampening=0.0, weight_decay=0.0, nesterov=False, foreach=False)
+    theta, b = th0.copy(), np.zeros(n)
+    for g in (g1, g2):
+        oracle.sgdm_begin_step(b, mu, lib=lib)
+        oracle.sgdm_fold(b, g, 1, 1.0, lib=lib)
+        oracle.sgdm_apply(theta, b, lr, 0.0, lib=lib)
+        p.grad = torch.from_numpy(g.copy())
+        opt.step()
+        assert np.array_equal(b, opt.state[p]["momentum_buffer"].numpy(), equal_nan=True), "SGD buffer with non-finite gradients"
+        assert np.array_equal(theta, p.detach().numpy(), equal_nan=True), "SGD parameters with non-finite gradients"
+    assert theta[0] == -inf and theta[1] == inf and theta[3] == -inf and np.isnan(theta[4]) and np.isfinite(theta[2])
+
+
 ALL_PINS = (
     pin_widening,
     pin_tiny_exact,
@@ -580,4 +635,5 @@ ALL_PINS = (
     pin_adamw_closed_forms,
     pin_sgdm_library,
     pin_sgdm_closed_forms,
+    pin_non_finite_values,
 )

@@ -74,6 +74,8 @@ MUTANTS = [
     ("sgdm_apply_sign", "theta[k] - decay - lr * b[k];", "theta[k] - decay + lr * b[k];", 0),
     ("sgdm_apply_no_lr", "theta[k] - decay - lr * b[k];", "theta[k] - decay - b[k];", 0),
     ("sgdm_apply_decay_without_lr", "double decay = lr * weight_decay * theta[k];", "double decay = weight_decay * theta[k];", 1),
+    ("adamw_zero_decay_forms_zero_times_theta", "if (weight_decay == 0.0) decay = 0.0;", "", 0),
+    ("sgdm_zero_decay_forms_zero_times_theta", "if (weight_decay == 0.0) decay = 0.0;", "", 1),
     ("sgdm_apply_decay_sign", "theta[k] - decay - lr * b[k];", "theta[k] + decay - lr * b[k];", 0),
 ]
 
