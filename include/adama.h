@@ -263,6 +263,17 @@ int adama_max_tensors_per_launch(void);
 void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
                   unsigned long long *big_launch_elems, int *policy_bits);
 
+/* Host-only: how many workgroups of a launch of op `op` over `launch_elems` elements one compute unit
+ * holds at once (0: as many as fit; -1 for an unknown op).  Part of the launch policy: see adama_tuning. */
+int adama_residency(int op, unsigned long long launch_elems);
+
+/* Host-only measurement aid, not for production use and not thread-safe: overrides, until the process
+ * ends, the number of workgroups per compute unit for launches of op `op` in size class `size_class`
+ * (0: under 2^20 elements, 1: up to about 100 M, 2: beyond); wgs_per_cu 0 lifts the bound, -1 restores
+ * the library's own choice.  Results never depend on it.  Used to produce the A/B tables of the
+ * launch policy. */
+void adama_debug_set_residency(int op, int size_class, int wgs_per_cu);
+
 /* Host-only: the chunk size (elements handled by one workgroup) the library uses for a launch of op
  * `op` (numbering as in adama_debug_walk) over tensors totalling `launch_elems` elements; 0 for an
  * unknown op.  For benchmark labels and profile filters. */

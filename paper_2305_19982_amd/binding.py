@@ -129,6 +129,10 @@ def load() -> ctypes.CDLL:
     lib.adama_last_error.argtypes = []
     lib.adama_max_tensors_per_launch.restype = i32
     lib.adama_max_tensors_per_launch.argtypes = []
+    lib.adama_residency.restype = i32
+    lib.adama_residency.argtypes = [i32, ctypes.c_ulonglong]
+    lib.adama_debug_set_residency.restype = None
+    lib.adama_debug_set_residency.argtypes = [i32, i32, i32]
     lib.adama_build_id.restype = ctypes.c_char_p
     lib.adama_build_id.argtypes = []
     lib.adama_launch_chunk.restype = i32
@@ -155,6 +159,14 @@ def _check(status: int) -> None:
 
 def adama_last_error() -> str:
     return load().adama_last_error().decode("utf-8", "replace")
+
+
+def adama_residency(op, launch_elems: int) -> int:
+    return int(load().adama_residency(OPS.get(op, op), int(launch_elems)))
+
+
+def adama_debug_set_residency(op, size_class: int, wgs_per_cu: int) -> None:
+    load().adama_debug_set_residency(OPS.get(op, op), size_class, wgs_per_cu)
 
 
 def adama_build_id() -> str:

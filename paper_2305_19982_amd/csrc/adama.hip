@@ -17,6 +17,7 @@ using namespace adama;
 static_assert(ADAMA_MAX_TENSORS_PER_LAUNCH == kMaxTensors, "header and kernel table size disagree");
 static_assert(sizeof(Table<kMaxTensors>) + sizeof(Scalars) <= 4096, "launch table must fit the kernel argument block");
 static_assert(sizeof(Desc) == 40, "descriptor layout");
+static_assert(kMaxTensors % 16 == 0, "the table search reads whole blocks of 16 entries");
 static_assert((int)ADAMA_F32 == kF32 && (int)ADAMA_BF16 == kBF16 && (int)ADAMA_F16 == kF16, "dtype codes");
 
 namespace {
@@ -61,27 +62,51 @@ constexpr uint64_t kHugeLaunchElems = 3u << 25;          // "huge" launches: at 
 // for decay (+5 %) and update (+2 %).  Launches under 2^20 elements are latency-bound and use 256 x 1.
 struct Policy {
     Shape small, big, huge;
+    uint64_t max_launch_elems;   // a list is cut so that no launch of this op exceeds this many elements (0: no such cut)
 };
 #ifndef ADAMA_POLICY_TABLE
-#define ADAMA_POLICY_TABLE {                                                         \
-    /* decay             */ {{256, 1}, {128, 1}, {256, 1}},                          \
-    /* fold              */ {{256, 1}, {128, 1}, {256, 4}},                          \
-    /* apply             */ {{256, 1}, {256, 1}, {256, 1}},                          \
-    /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}},                          \
-    /* fold_last_apply   */ {{256, 1}, {256, 1}, {256, 1}},                          \
-    /* rescale_apply     */ {{256, 1}, {256, 1}, {256, 1}},                          \
-    /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}},                          \
-    /* sgd fold          */ {{256, 1}, {256, 2}, {256, 2}},                          \
-    /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}},                          \
-    /* sgd fold_first    */ {{256, 1}, {256, 2}, {256, 2}},                          \
-    /* sgd fold_last_apply */ {{256, 1}, {256, 2}, {256, 2}},                        \
+#define ADAMA_POLICY_TABLE {                                                            \
+    /* decay             */ {{256, 1}, {128, 2}, {128, 2}, ADAMA_DECAY_LAUNCH_CAP},     \
+    /* fold              */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
+    /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
+    /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
+    /* fold_last_apply   */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
+    /* rescale_apply     */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
+    /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
+    /* sgd fold          */ {{256, 1}, {256, 2}, {256, 2}, 0},                          \
+    /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
+    /* sgd fold_first    */ {{256, 1}, {256, 2}, {256, 2}, 0},                          \
+    /* sgd fold_last_apply */ {{256, 1}, {256, 2}, {256, 2}, 0},                        \
 }
+#endif
+#ifndef ADAMA_DECAY_LAUNCH_CAP
+#define ADAMA_DECAY_LAUNCH_CAP (1ull << 26)
 #endif
 constexpr Policy kPolicy[kNumOps] = ADAMA_POLICY_TABLE;
 
+// Residency override for measurements (adama_debug_set_residency): -1 = the policy's own value.
+int g_residency_override[kNumOps][3];
+bool g_residency_override_set = false;
+
 Shape launch_shape_for(int op, uint64_t elems)
 {
-    return elems >= kHugeLaunchElems ? kPolicy[op].huge : elems >= kBigLaunchElems ? kPolicy[op].big : kPolicy[op].small;
+    const int cls = elems >= kHugeLaunchElems ? 2 : elems >= kBigLaunchElems ? 1 : 0;
+    Shape s = cls == 2 ? kPolicy[op].huge : cls == 1 ? kPolicy[op].big : kPolicy[op].small;
+    if (g_residency_override_set && g_residency_override[op][cls] >= 0) s.wgs = g_residency_override[op][cls];
+    return s;
+}
+
+// A compute unit of this chip has 160 KiB of LDS.  The kernels use none of it; a launch asks for an
+// (unused) share of it per workgroup only to bound how many of its workgroups a compute unit holds at
+// once, which bounds the number of memory requests in flight.  Measured: a streaming kernel at full
+// residency (32 wavefronts per compute unit) delivers 3..5 % less than one held to 8..16 wavefronts;
+// with too many requests queued the memory system reorders across too wide an address window.
+constexpr uint32_t kLdsPerComputeUnit = 160u * 1024u;
+uint32_t residency_lds_bytes(int wgs_per_cu)
+{
+    if (wgs_per_cu <= 0) return 0;
+    const uint32_t share = (kLdsPerComputeUnit / (uint32_t)wgs_per_cu) & ~1023u;   // whole KiB, rounded down
+    return share > 65536u ? 65536u : share;                                      // 64 KiB needs no opt-in
 }
 
 uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF32 ? 4u : 2u; }
@@ -103,7 +128,9 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
         std::memset(&b.tab, 0, sizeof b.tab);
         uint64_t elems = 0;
         int k = 0;
-        while (i + k < count && k < kMaxTensors && elems + descs[i + k].n <= kMaxLaunchElems) {
+        const uint64_t cap = kPolicy[op].max_launch_elems ? kPolicy[op].max_launch_elems : kMaxLaunchElems;
+        // a tensor longer than the op's cut still goes into a launch of its own (kMaxLaunchElems bounds every tensor)
+        while (i + k < count && k < kMaxTensors && (elems + descs[i + k].n <= cap || (k == 0 && descs[i].n <= kMaxLaunchElems))) {
             b.tab.t[k] = descs[i + k];
             elems += descs[i + k].n;
             ++k;
@@ -114,9 +141,9 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
         for (int j = 0; j < k; ++j) {
             b.tab.chunk_start[j] = (uint32_t)start;
             start += chunks_of(misalign_elems(b.tab.t[j].s[0]), b.tab.t[j].n, chunk);
+            b.tab.next_start[j] = (uint32_t)start;
         }
-        b.tab.chunk_start[k] = (uint32_t)start;
-        for (int j = k + 1; j < kMaxTensors + 17; ++j) b.tab.chunk_start[j] = 0xFFFFFFFFu;
+        for (int j = k; j < kMaxTensors + 16; ++j) b.tab.next_start[j] = 0xFFFFFFFFu;
         b.tab.count = (uint32_t)k;
         b.tab.total = (uint32_t)start;
         b.total = (uint32_t)start;
@@ -134,10 +161,11 @@ template <int OpK, int GT, int BLOCK, int U>
 void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
     static_assert(BLOCK % 64 == 0 && BLOCK <= kMaxBlock && U >= 1, "workgroup shape");
+    const uint32_t lds = residency_lds_bytes(b.shape.wgs);
     if (b.tab.count == 1)
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, true>), dim3(b.total), dim3(BLOCK), 0, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, true>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
     else
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, false>), dim3(b.total), dim3(BLOCK), 0, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, false>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
 }
 
 // Picks the instantiation for the batch's shape, which is one of the op's three.
@@ -402,11 +430,27 @@ int adama_launch_chunk(int op, unsigned long long launch_elems)
 void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
                   unsigned long long *big_launch_elems, int *policy_bits)
 {
-    const Shape s = (op >= 0 && op < kNumOps) ? launch_shape_for(op, launch_elems) : Shape{0, 0};
+    const Shape s = (op >= 0 && op < kNumOps) ? launch_shape_for(op, launch_elems) : Shape{0, 0, 0};
     if (block) *block = s.block;
     if (groups_per_thread) *groups_per_thread = s.u;
     if (big_launch_elems) *big_launch_elems = kBigLaunchElems;
     if (policy_bits) *policy_bits = kNtPolicy;
+}
+
+void adama_debug_set_residency(int op, int size_class, int wgs_per_cu)
+{
+    if (!g_residency_override_set) {
+        for (int o = 0; o < kNumOps; ++o)
+            for (int c = 0; c < 3; ++c) g_residency_override[o][c] = -1;
+        g_residency_override_set = true;
+    }
+    if (op < 0 || op >= kNumOps || size_class < 0 || size_class > 2) return;
+    g_residency_override[op][size_class] = wgs_per_cu;
+}
+
+int adama_residency(int op, unsigned long long launch_elems)
+{
+    return (op >= 0 && op < kNumOps) ? launch_shape_for(op, launch_elems).wgs : -1;
 }
 
 adama_status adama_fold_opt_multi(const adama_tensor *list, int count, adama_dtype gdt, int N, double beta1,
@@ -650,7 +694,7 @@ adama_status adama_debug_walk(const adama_update_tensor *list, int count, int op
             const uint32_t cnt = b.tab.count;
             const int base = i0 + first;   // list index of the batch's first tensor
             for (uint32_t c = 0; c < b.total; ++c) {
-                const uint32_t k = cnt > 1 ? find_tensor(b.tab.chunk_start, c) : 0u;
+                const uint32_t k = cnt > 1 ? find_tensor(b.tab.next_start, c) : 0u;
                 const Desc &d = b.tab.t[k];
                 const uint64_t lc = c - b.tab.chunk_start[k];
                 const uint32_t pre = misalign_elems(d.s[0]);

@@ -63,9 +63,10 @@ ADAMA_HD constexpr int op_store_mask(int op)
 }
 
 // Shape of a launch's workgroups: `block` threads, each moving `u` 4-element groups per array, so one
-// workgroup handles a chunk of block * 4 * u elements.
+// workgroup handles a chunk of block * 4 * u elements; `wgs` = how many workgroups of the launch a
+// compute unit may hold at once (0: as many as fit).
 struct Shape {
-    int block, u;
+    int block, u, wgs;
 };
 ADAMA_HD constexpr uint32_t chunk_elems(Shape s) { return (uint32_t)(s.block * kGroup * s.u); }
 ADAMA_HD constexpr bool same_shape(Shape a, Shape b) { return a.block == b.block && a.u == b.u; }
@@ -79,13 +80,14 @@ struct Desc {
 
 template <int MaxT>
 struct Table {
+    // next_start[k] = number of chunks of tensors 0..k (= first chunk of tensor k+1; [count-1] = total);
+    // entries from [count] on = 0xFFFFFFFF.  It leads the table so that the first 16-entry block of
+    // find_tensor is one aligned 64-byte read of the kernel argument block.
+    uint32_t next_start[MaxT + 16];
     Desc t[MaxT];
-    // chunk_start[k] = first chunk of tensor k; [count] = total; entries past [count] = 0xFFFFFFFF.
-    // Sized so that the 16-wide search blocks of find_tensor never read past the array.
-    uint32_t chunk_start[MaxT + 17];
+    uint32_t chunk_start[MaxT];       // chunk_start[k] = first chunk of tensor k
     uint32_t count;
-    uint32_t total;                   // == chunk_start[count]
-    uint32_t pad;
+    uint32_t total;                   // number of chunks of the launch
 };
 
 // Misalignment of the first state array, in float32 elements (0..3).
@@ -108,14 +110,15 @@ ADAMA_HD uint64_t chunks_of(uint32_t pre, uint64_t n, uint32_t chunk)
     return n == 0 ? 0 : (pre + n + chunk - 1) / chunk;
 }
 
-// Largest k in [0, count) with start[k] <= c, given start[0] == 0 <= c < start[count] and every entry
-// past [count] equal to 0xFFFFFFFF.  Zero-length tensors (start[k] == start[k+1]) are skipped by the
-// tie rule.  start[] is non-decreasing, so k is the number of entries start[1..] that are <= c.
-// They are counted in blocks of 16 whose loads do not depend on one another (one scalar-cache latency
-// per block instead of one per bisection step); a block with fewer than 16 hits ends the search, so
-// the tensor count itself is never read.
-template <typename StartArray>
-ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t c)
+// The tensor that owns chunk c, given 0 <= c < total: the number of tensors that end at or before c,
+// i.e. the number of entries of next[] that are <= c (next[] is non-decreasing and every entry past
+// the launch's tensors is 0xFFFFFFFF).  A zero-length tensor ends where it starts, so it is counted
+// together with its predecessor and never owns a chunk.  Entries are counted in blocks of 16 whose
+// loads do not depend on one another (one scalar-cache latency per block instead of one per bisection
+// step); a block with fewer than 16 hits ends the search, so the tensor count itself is never read
+// and a launch of up to 16 tensors needs a single block.
+template <typename NextArray>
+ADAMA_HD uint32_t find_tensor(const NextArray &next, uint32_t c)
 {
     uint32_t k = 0;
     for (uint32_t base = 0;; base += 16) {
@@ -123,7 +126,7 @@ ADAMA_HD uint32_t find_tensor(const StartArray &start, uint32_t c)
 #if defined(__HIPCC__)
 #pragma unroll
 #endif
-        for (uint32_t j = 0; j < 16; ++j) hits += (start[base + j + 1] <= c) ? 1u : 0u;
+        for (uint32_t j = 0; j < 16; ++j) hits += (next[base + j] <= c) ? 1u : 0u;
         k += hits;
         if (hits < 16) break;
     }

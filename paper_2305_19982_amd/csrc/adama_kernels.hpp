@@ -176,6 +176,40 @@ __device__ __forceinline__ void element_op(float (&s)[3], float g, const Scalars
     }
 }
 
+// The table search of adama_index.hpp's find_tensor, spelled for the scalar unit: the chunk number is
+// wave-uniform, so every compare runs on the scalar ALU.  Each entry costs one compare and one
+// add-with-carry (the compare's result is the carry); written this way the compiler cannot route half of
+// the compares through the vector unit and back, which it does for the portable form.  Same result as
+// find_tensor for every input (the GPU tests compare list launches with single-tensor launches bitwise).
+#ifndef ADAMA_SEARCH
+#define ADAMA_SEARCH 1
+#endif
+__device__ __forceinline__ uint32_t find_tensor_scalar(const uint32_t *next, uint32_t c)
+{
+#if ADAMA_SEARCH == 0
+    return find_tensor(next, c);
+#else
+    typedef uint32_t u32x16 __attribute__((ext_vector_type(16), aligned(4)));
+    uint32_t k = 0;
+    for (uint32_t base = 0;; base += 16) {
+        const u32x16 block = *reinterpret_cast<const u32x16 *>(next + base);     // one 64-byte scalar load
+        uint32_t hits = 0;
+#pragma unroll
+        for (uint32_t j = 0; j < 16; ++j) {
+            const uint32_t s = block[j];
+#if ADAMA_SEARCH == 1
+            asm("s_cmp_le_u32 %1, %2\n\ts_addc_u32 %0, %0, 0" : "+s"(hits) : "s"(s), "s"(c) : "scc");
+#else
+            hits += 1u - ((c - s) >> 31);       // entries and c stay below 2^31; sentinels are 0xFFFFFFFF: c + 1 < 2^31
+#endif
+        }
+        k += hits;
+        if (hits < 16) break;
+    }
+    return k;
+#endif
+}
+
 // Picks the aligned or the element-aligned flavour of a vector type.
 template <bool ALIGNED, typename A, typename U_> struct Pick { using T = A; };
 template <typename A, typename U_> struct Pick<false, A, U_> { using T = U_; };
@@ -303,7 +337,7 @@ __global__ void __launch_bounds__(BLOCK) multi_tensor_kernel(const Table<kMaxTen
     const uint32_t c = blockIdx.x;
     constexpr uint32_t chunk = BLOCK * kGroup * U;
     constexpr uint32_t g_bytes = !op_has_grad(OpK) ? 0u : GT == kF32 ? 4u : 2u;
-    const uint32_t k = SINGLE ? 0u : find_tensor(tab.chunk_start, c);
+    const uint32_t k = SINGLE ? 0u : find_tensor_scalar(tab.next_start, c);
     const Desc d = tab.t[k];
     const uint64_t lc = SINGLE ? c : c - tab.chunk_start[k];
     const uint32_t pre = misalign_elems(d.s[0]);

@@ -127,6 +127,12 @@ def _device_lib():
         _device.synth_stream_probe.restype = ctypes.c_int
         _device.synth_stream_probe.argtypes = [ctypes.c_int, ctypes.c_int] + [ctypes.c_void_p] * 5 + [ctypes.c_uint64,
                                                                                                     ctypes.c_void_p]
+        _device.synth_stream_probe_shape.restype = ctypes.c_int
+        _device.synth_stream_probe_shape.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_uint] + [
+            ctypes.c_void_p] * 5 + [ctypes.c_uint64, ctypes.c_void_p]
+        _device.synth_stream_probe_persistent.restype = ctypes.c_int
+        _device.synth_stream_probe_persistent.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint] + [
+            ctypes.c_void_p] * 5 + [ctypes.c_uint64, ctypes.c_void_p]
         _device.synth_stream_probe_bytes.restype = ctypes.c_int
         _device.synth_stream_probe_bytes.argtypes = [ctypes.c_int]
     return _device
@@ -141,13 +147,25 @@ def stream_probe_bytes(mode: str) -> int:
     return int(_device_lib().synth_stream_probe_bytes(PROBE_MODES[mode]))
 
 
-def stream_probe(mode: str, block: int, g: int, a0: int, a1: int, a2: int, sink: int, n: int, stream: int) -> None:
-    """Enqueue one probe launch over n elements (a multiple of block*4) of device arrays at the given addresses."""
-    rc = _device_lib().synth_stream_probe(PROBE_MODES[mode], block, ctypes.c_void_p(g), ctypes.c_void_p(a0),
-                                          ctypes.c_void_p(a1), ctypes.c_void_p(a2), ctypes.c_void_p(sink), n,
-                                          ctypes.c_void_p(stream))
+def stream_probe(mode: str, block: int, g: int, a0: int, a1: int, a2: int, sink: int, n: int, stream: int,
+                 lds_bytes: int = 0, groups: int = 1) -> None:
+    """Enqueue one probe launch over n elements (a multiple of block*4*groups) of device arrays at the given
+    addresses; lds_bytes of unused LDS per workgroup cap the number of workgroups resident on a compute unit."""
+    rc = _device_lib().synth_stream_probe_shape(PROBE_MODES[mode], block, groups, lds_bytes, ctypes.c_void_p(g),
+                                                ctypes.c_void_p(a0), ctypes.c_void_p(a1), ctypes.c_void_p(a2),
+                                                ctypes.c_void_p(sink), n, ctypes.c_void_p(stream))
     if rc:
-        raise RuntimeError(f"synth_stream_probe({mode}, block={block}, n={n}) failed ({rc})")
+        raise RuntimeError(f"synth_stream_probe({mode}, block={block}, groups={groups}, lds={lds_bytes}, n={n}) failed ({rc})")
+
+
+def stream_probe_persistent(mode: str, block: int, grid: int, g: int, a0: int, a1: int, a2: int, sink: int, n: int,
+                            stream: int) -> None:
+    """The same streams from a persistent grid of `grid` workgroups with the next chunk's loads issued early."""
+    rc = _device_lib().synth_stream_probe_persistent(PROBE_MODES[mode], block, grid, ctypes.c_void_p(g),
+                                                     ctypes.c_void_p(a0), ctypes.c_void_p(a1), ctypes.c_void_p(a2),
+                                                     ctypes.c_void_p(sink), n, ctypes.c_void_p(stream))
+    if rc:
+        raise RuntimeError(f"synth_stream_probe_persistent({mode}, block={block}, grid={grid}, n={n}) failed ({rc})")
 
 
 def copy_device(dst: int, src: int, nbytes: int, stream: int) -> None:

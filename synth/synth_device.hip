@@ -59,37 +59,59 @@ extern "C" int synth_copy_device(void *dst, const void *src, uint64_t bytes, voi
 typedef uint32_t synth_u32x2 __attribute__((ext_vector_type(2)));
 #define SYNTH_GLOBAL __attribute__((address_space(1)))
 
-template <int BLOCK, int G16, int G32, int RW, int RO, int WO>
+template <int BLOCK, int U, int G16, int G32, int RW, int RO, int WO>
 __global__ void __launch_bounds__(BLOCK) synth_stream_probe_kernel(const void *g, float *a0, float *a1, float *a2, float *sink)
 {
     static_assert(RW + RO + WO <= 3, "three float32 arrays at most");
-    const uint64_t e0 = (uint64_t)blockIdx.x * (BLOCK * 4);
-    const uint32_t i = threadIdx.x;
+    const uint64_t e0 = (uint64_t)blockIdx.x * (BLOCK * 4 * U);
     float *arr[3] = {a0, a1, a2};
-    synth_f32x4 x[3];
-    synth_f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-    if (G16) {
-        synth_u32x2 w = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_u32x2 *)((const uint16_t *)g + e0) + i);
-        acc.x += __builtin_bit_cast(float, w.x << 16);
-        acc.y += __builtin_bit_cast(float, w.y << 16);
+    synth_f32x4 x[3][U];
+    synth_f32x4 acc[U];
+    /* all loads of the chunk first, then, group by group, the stores */
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = u * BLOCK + threadIdx.x;
+        acc[u] = synth_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (G16) {
+            synth_u32x2 w = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_u32x2 *)((const uint16_t *)g + e0) + i);
+            acc[u].x += __builtin_bit_cast(float, w.x << 16);
+            acc[u].y += __builtin_bit_cast(float, w.y << 16);
+        }
+        if (G32) acc[u] += __builtin_nontemporal_load((const SYNTH_GLOBAL synth_f32x4 *)((const float *)g + e0) + i);
+#pragma unroll
+        for (int k = 0; k < RW + RO; ++k) x[k][u] = __builtin_nontemporal_load((SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
     }
-    if (G32) acc += __builtin_nontemporal_load((const SYNTH_GLOBAL synth_f32x4 *)((const float *)g + e0) + i);
+    /* every load above is issued before anything below: without this the instruction scheduler may sink a
+       load behind the first use of another one, which doubles a workgroup's time in flight */
+    __builtin_amdgcn_sched_barrier(0);
+    float keep = 0.0f;
 #pragma unroll
-    for (int k = 0; k < RW + RO; ++k) x[k] = __builtin_nontemporal_load((SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+    for (int u = 0; u < U; ++u) {
+        const uint32_t i = u * BLOCK + threadIdx.x;
 #pragma unroll
-    for (int k = RW; k < RW + RO; ++k) acc += x[k];
+        for (int k = RW; k < RW + RO; ++k) acc[u] += x[k][u];
 #pragma unroll
-    for (int k = 0; k < RW; ++k) __builtin_nontemporal_store(x[k] + acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+        for (int k = 0; k < RW; ++k) __builtin_nontemporal_store(x[k][u] + acc[u], (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
 #pragma unroll
-    for (int k = RW + RO; k < RW + RO + WO; ++k) __builtin_nontemporal_store(acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
-    if (RW + WO == 0 && acc.x + acc.y + acc.z + acc.w == 12345.678f) *sink = acc.x;   /* keeps read-only loads alive */
+        for (int k = RW + RO; k < RW + RO + WO; ++k) __builtin_nontemporal_store(acc[u], (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e0) + i);
+        keep += acc[u].x + acc[u].y + acc[u].z + acc[u].w;
+    }
+    if (RW + WO == 0 && keep == 12345.678f) *sink = keep;   /* keeps read-only loads alive */
 }
 
-template <int BLOCK>
-static void synth_stream_probe_launch(int mode, unsigned grid, const void *g, float *a0, float *a1, float *a2, float *sink, hipStream_t s)
+template <int BLOCK, int U>
+static int synth_stream_probe_launch(int mode, unsigned grid, unsigned lds_bytes, const void *g, float *a0, float *a1, float *a2,
+                                     float *sink, hipStream_t s)
 {
-#define SYNTH_PROBE(G16, G32, RW, RO, WO) \
-    hipLaunchKernelGGL((synth_stream_probe_kernel<BLOCK, G16, G32, RW, RO, WO>), dim3(grid), dim3(BLOCK), 0, s, g, a0, a1, a2, sink)
+    /* more than 64 KiB of dynamic LDS has to be asked for per kernel */
+#define SYNTH_PROBE(G16, G32, RW, RO, WO)                                                                                   \
+    do {                                                                                                                    \
+        auto kern = synth_stream_probe_kernel<BLOCK, U, G16, G32, RW, RO, WO>;                                              \
+        if (lds_bytes > 65536u &&                                                                                           \
+            hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes) != hipSuccess) \
+            return 2;                                                                                                       \
+        hipLaunchKernelGGL(kern, dim3(grid), dim3(BLOCK), lds_bytes, s, g, a0, a1, a2, sink);                               \
+    } while (0)
     switch (mode) {
     case 0: SYNTH_PROBE(1, 0, 0, 2, 0); break;   /* read only, fold's inputs: g16, m, v         10 B/element */
     case 1: SYNTH_PROBE(0, 0, 0, 0, 2); break;   /* write only, fold's outputs: m, v             8 */
@@ -99,9 +121,88 @@ static void synth_stream_probe_launch(int mode, unsigned grid, const void *g, fl
     case 5: SYNTH_PROBE(0, 0, 1, 2, 0); break;   /* update mix: r theta,m,v  w theta            16 */
     case 6: SYNTH_PROBE(0, 0, 3, 0, 0); break;   /* rescale mix: r and w theta,m,v              24 */
     case 7: SYNTH_PROBE(0, 0, 0, 3, 0); break;   /* read only, three fp32 arrays                12 */
-    default: break;
+    default: return 1;
     }
 #undef SYNTH_PROBE
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+/* The same streams from a persistent grid: `grid` workgroups, workgroup w taking chunks w, w + grid, ...
+   of BLOCK*4 elements one after the other (no workgroup start-up between chunks; the number of
+   workgroups, not the hardware's residency limit, sets how many requests are in flight). */
+template <int BLOCK, int G16, int G32, int RW, int RO, int WO>
+__global__ void __launch_bounds__(BLOCK) synth_stream_probe_persistent_kernel(const void *g, float *a0, float *a1, float *a2,
+                                                                              float *sink, uint32_t nchunks)
+{
+    float *arr[3] = {a0, a1, a2};
+    const uint32_t i = threadIdx.x;
+    float keep = 0.0f;
+#pragma unroll 1
+    for (uint32_t c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const uint64_t e = (uint64_t)c * (BLOCK * 4);
+        synth_f32x4 x[3];
+        synth_f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+        synth_u32x2 w16 = {0u, 0u};
+        synth_f32x4 w32 = acc;
+        if (G16) w16 = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_u32x2 *)((const uint16_t *)g + e) + i);
+        if (G32) w32 = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_f32x4 *)((const float *)g + e) + i);
+#pragma unroll
+        for (int k = 0; k < RW + RO; ++k) x[k] = __builtin_nontemporal_load((SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e) + i);
+        __builtin_amdgcn_sched_barrier(0);
+        if (G16) {
+            acc.x += __builtin_bit_cast(float, w16.x << 16);
+            acc.y += __builtin_bit_cast(float, w16.y << 16);
+        }
+        if (G32) acc += w32;
+#pragma unroll
+        for (int k = RW; k < RW + RO; ++k) acc += x[k];
+#pragma unroll
+        for (int k = 0; k < RW; ++k) __builtin_nontemporal_store(x[k] + acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e) + i);
+#pragma unroll
+        for (int k = RW + RO; k < RW + RO + WO; ++k) __builtin_nontemporal_store(acc, (SYNTH_GLOBAL synth_f32x4 *)(arr[k] + e) + i);
+        keep += acc.x + acc.y + acc.z + acc.w;
+    }
+    if (RW + WO == 0 && keep == 12345.678f) *sink = keep;
+}
+
+template <int BLOCK>
+static int synth_stream_probe_persistent_launch(int mode, unsigned grid, const void *g, float *a0, float *a1, float *a2, float *sink,
+                                                uint32_t nchunks, hipStream_t s)
+{
+#define SYNTH_PROBE(G16, G32, RW, RO, WO) \
+    hipLaunchKernelGGL((synth_stream_probe_persistent_kernel<BLOCK, G16, G32, RW, RO, WO>), dim3(grid), dim3(BLOCK), 0, s, g, a0, a1, a2, sink, nchunks)
+    switch (mode) {
+    case 0: SYNTH_PROBE(1, 0, 0, 2, 0); break;
+    case 1: SYNTH_PROBE(0, 0, 0, 0, 2); break;
+    case 2: SYNTH_PROBE(1, 0, 2, 0, 0); break;
+    case 3: SYNTH_PROBE(0, 1, 2, 0, 0); break;
+    case 4: SYNTH_PROBE(0, 0, 2, 0, 0); break;
+    case 5: SYNTH_PROBE(0, 0, 1, 2, 0); break;
+    case 6: SYNTH_PROBE(0, 0, 3, 0, 0); break;
+    case 7: SYNTH_PROBE(0, 0, 0, 3, 0); break;
+    default: return 1;
+    }
+#undef SYNTH_PROBE
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+/* Enqueue one persistent probe launch of `grid` workgroups of `block` threads (64, 128 or 256) over the first n
+   elements (a multiple of block*4); other arguments as synth_stream_probe_shape. */
+extern "C" int synth_stream_probe_persistent(int mode, int block, unsigned grid, const void *g, float *a0, float *a1, float *a2,
+                                             float *sink, uint64_t n, void *stream)
+{
+    if (n == 0) return 0;
+    if (mode < 0 || mode > 7 || grid == 0 || !a0 || !a1 || !a2 || !sink) return 1;
+    if (block != 64 && block != 128 && block != 256) return 1;
+    const uint64_t chunk = (uint64_t)block * 4;
+    if (n % chunk || n / chunk > 0x7FFFFFFFull) return 1;
+    if ((mode == 0 || mode == 2 || mode == 3) && !g) return 1;
+    if (((uintptr_t)g | (uintptr_t)a0 | (uintptr_t)a1 | (uintptr_t)a2) & 15) return 1;
+    const uint32_t nchunks = (uint32_t)(n / chunk);
+    hipStream_t s = (hipStream_t)stream;
+    if (block == 64) return synth_stream_probe_persistent_launch<64>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
+    if (block == 128) return synth_stream_probe_persistent_launch<128>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
+    return synth_stream_probe_persistent_launch<256>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
 }
 
 /* Bytes per element of a probe mode, 0 for an unknown mode. */
@@ -111,18 +212,36 @@ extern "C" int synth_stream_probe_bytes(int mode)
     return mode >= 0 && mode < 8 ? bytes[mode] : 0;
 }
 
-/* Enqueue one probe launch over the first n elements (n a multiple of block*4, block 128 or 256; arrays
-   16-byte aligned device memory of at least n elements each; g may be NULL for modes without one). */
+/* Enqueue one probe launch over the first n elements: workgroups of `block` threads (64, 128, 256, 512 or
+   1024), each thread moving `groups` 4-element groups per array (1, 2 or 4), one workgroup per chunk of
+   block*4*groups elements; n must be a multiple of the chunk; arrays are 16-byte aligned device memory of
+   at least n elements each; g may be NULL for modes without one.  lds_bytes of (unused) dynamic LDS per
+   workgroup (at most 160 KiB) limit how many workgroups a compute unit holds at once: the knob for
+   measuring how the number of requests in flight changes the delivered bandwidth.
+   Returns 0, 1 on a bad argument, 2 on a HIP error. */
+extern "C" int synth_stream_probe_shape(int mode, int block, int groups, unsigned lds_bytes, const void *g, float *a0, float *a1,
+                                        float *a2, float *sink, uint64_t n, void *stream)
+{
+    if (n == 0) return 0;
+    if (mode < 0 || mode > 7 || groups < 1 || block < 64 || !a0 || !a1 || !a2 || !sink || lds_bytes > 160u * 1024u) return 1;
+    const uint64_t chunk = (uint64_t)block * 4 * (uint64_t)groups;
+    if (n % chunk || n / chunk > 0x7FFFFFFFull) return 1;
+    if ((mode == 0 || mode == 2 || mode == 3) && !g) return 1;
+    if (((uintptr_t)g | (uintptr_t)a0 | (uintptr_t)a1 | (uintptr_t)a2) & 15) return 1;
+    const unsigned grid = (unsigned)(n / chunk);
+    hipStream_t s = (hipStream_t)stream;
+#define SYNTH_SHAPE(B, G) if (block == B && groups == G) return synth_stream_probe_launch<B, G>(mode, grid, lds_bytes, g, a0, a1, a2, sink, s)
+    SYNTH_SHAPE(64, 1); SYNTH_SHAPE(64, 2); SYNTH_SHAPE(64, 4);
+    SYNTH_SHAPE(128, 1); SYNTH_SHAPE(128, 2); SYNTH_SHAPE(128, 4);
+    SYNTH_SHAPE(256, 1); SYNTH_SHAPE(256, 2); SYNTH_SHAPE(256, 4);
+    SYNTH_SHAPE(512, 1); SYNTH_SHAPE(512, 2);
+    SYNTH_SHAPE(1024, 1);
+#undef SYNTH_SHAPE
+    return 1;
+}
+
 extern "C" int synth_stream_probe(int mode, int block, const void *g, float *a0, float *a1, float *a2, float *sink,
                                   uint64_t n, void *stream)
 {
-    if (n == 0) return 0;
-    if (mode < 0 || mode > 7 || (block != 128 && block != 256) || n % (uint64_t)(block * 4) || !a0 || !a1 || !a2 || !sink)
-        return 1;
-    if ((mode == 0 || mode == 2 || mode == 3) && !g) return 1;
-    if ((((uintptr_t)g | (uintptr_t)a0 | (uintptr_t)a1 | (uintptr_t)a2) & 15) || n / (uint64_t)(block * 4) > 0x7FFFFFFFull) return 1;
-    const unsigned grid = (unsigned)(n / (uint64_t)(block * 4));
-    if (block == 128) synth_stream_probe_launch<128>(mode, grid, g, a0, a1, a2, sink, (hipStream_t)stream);
-    else synth_stream_probe_launch<256>(mode, grid, g, a0, a1, a2, sink, (hipStream_t)stream);
-    return hipGetLastError() == hipSuccess ? 0 : 2;
+    return synth_stream_probe_shape(mode, block, 1, 0, g, a0, a1, a2, sink, n, stream);
 }
