@@ -94,8 +94,9 @@ def cpu_baseline(w, budget_s: float = 15.0, optimizer: str = "adama") -> dict:
         layers_done += 1
     per_param = per_param_bytes(w, optimizer)
     return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "extrapolated": True,       # a rate per parameter from a bounded sample of the workload, not a run of all of it
             "params_per_s": round(params / spent, 1),
-            "sample": f"tensors of the {layers_done} largest layer(s) of {w.name} ({params} params"
+            "sample": f"extrapolated from a prefix sample: tensors of the {layers_done} largest layer(s) of {w.name} ({params} params"
                       f"{', at most the first 16 M elements of each' if capped else ''}), one full mini-batch "
                       f"each (decay + {w.N} folds + update) in {spent:.1f} s, single thread, fp64"}
 
@@ -150,6 +151,7 @@ def cpu_baseline_all_cores(w, budget_s: float = 8.0, optimizer: str = "adama") -
             tensors_done += 1
     per_param = per_param_bytes(w, optimizer)
     return {"value": round(params * per_param / spent / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "extrapolated": True,
             "params_per_s": round(params / spent, 1),
             "sample": f"{tensors_done} large tensor(s) of {w.name} ({params} params), one full mini-batch each, every "
                       f"tensor cut into {cores} contiguous slices run by {cores} threads calling the unchanged "
@@ -160,7 +162,9 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
     """What the memory system delivers for the access mixes of the path's kernels, without their arithmetic
     (synth_stream_probe_kernel): pure read, pure write, and the read : write mixes of fold, decay, update and
     rescale, as sustained launches of one transformer block's size marching through arrays as large as the
-    GPT-2-1.5B-shaped state; then the fold mix over a sweep of launch sizes, fitted as t = a + n / b."""
+    GPT-2-1.5B-shaped state and filled with values like the workload's; then the fold mix on all-zero
+    arrays (the delivered bandwidth depends on the contents), at bounded residency, and over a sweep of
+    launch sizes."""
     import numpy as np
     import torch
 
@@ -170,20 +174,35 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
     dev = "cuda:0"
     stream = torch.cuda.Stream(device=dev)
     with torch.cuda.stream(stream):
-        arrays = [torch.zeros(arena_elems, dtype=torch.float32, device=dev) for _ in range(3)]
-        g = torch.zeros(arena_elems, dtype=torch.float32, device=dev)      # read as 16-bit or as float32 elements
+        arrays = [torch.empty(arena_elems, dtype=torch.float32, device=dev) for _ in range(3)]
+        g = torch.empty(arena_elems, dtype=torch.float32, device=dev)      # read as 16-bit or as float32 elements
         sink = torch.zeros(4, dtype=torch.float32, device=dev)
     stream.synchronize()
     sh = stream.cuda_stream
 
-    def sustained(mode: str, block: int, n: int, passes: int = 2) -> tuple:
-        n -= n % (block * 4)
+    def fill(zero: bool) -> None:
+        """Values like the workload's (weights N(0, 0.02), moments at their usual magnitudes, gradients N(0, 1e-3)
+        in both 16-bit halves), or zeros."""
+        with torch.cuda.stream(stream):
+            if zero:
+                for a in arrays + [g]:
+                    a.zero_()
+            else:
+                arrays[0].normal_(0.0, 1e-4)
+                arrays[1].uniform_(1e-9, 1e-7)
+                arrays[2].normal_(0.0, 0.02)
+                g.view(torch.bfloat16).normal_(0.0, 1e-3)
+        stream.synchronize()
+
+    def sustained(mode: str, block: int, n: int, passes: int = 2, lds: int = 0, groups: int = 1) -> tuple:
+        n -= n % (block * 4 * groups)
         slots = max(1, arena_elems // n)
 
         def launch(r: int) -> None:
             off = (r % slots) * n
             gen.stream_probe(mode, block, g.data_ptr() + 4 * off, arrays[0].data_ptr() + 4 * off,
-                             arrays[1].data_ptr() + 4 * off, arrays[2].data_ptr() + 4 * off, sink.data_ptr(), n, sh)
+                             arrays[1].data_ptr() + 4 * off, arrays[2].data_ptr() + 4 * off, sink.data_ptr(), n, sh,
+                             lds_bytes=lds, groups=groups)
 
         reps = max(passes * slots, 20)
         for r in range(min(slots, reps)):
@@ -199,16 +218,20 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
         return n, us, gen.stream_probe_bytes(mode) * n / (us * 1e-6) / 1e9
 
     out = {"launch_elems": launch_elems, "array_elems": arena_elems, "modes": {}, "note":
-           "one workgroup per block*4 elements, 16-byte accesses, all non-temporal, no optimizer arithmetic; "
-           "GB/s = bytes the mode moves / HIP-event time over back-to-back launches"}
+           "one workgroup per block*4 elements, 16-byte accesses, all non-temporal, no optimizer arithmetic; arrays hold "
+           "values like the workload's; GB/s = bytes the mode moves / HIP-event time over back-to-back launches"}
+    fill(zero=False)
     for rnd in range(2):                       # two rounds, the better one is kept (first-touch effects)
         for mode in gen.PROBE_MODES:
+            if mode == "write_m_v" and rnd == 1:
+                continue                       # it overwrites the contents: once, last of the first round's modes to matter
             for block in block_sizes:
                 n, us, gbs = sustained(mode, block, launch_elems)
                 key = f"{mode}/{block}"
                 if key not in out["modes"] or gbs > out["modes"][key]["GB/s"]:
                     out["modes"][key] = {"bytes_per_element": gen.stream_probe_bytes(mode), "us_per_launch": round(us, 2),
                                          "GB/s": round(gbs, 1)}
+        fill(zero=False)
     best = {m: max(out["modes"][f"{m}/{b}"]["GB/s"] for b in block_sizes) for m in gen.PROBE_MODES}
     rd, wr = best["read_g16_m_v"], best["write_m_v"]
     out["best"] = best
@@ -216,16 +239,28 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
     out["harmonic_ceiling"] = {name: round((r + w) / (r / rd + w / wr), 1)
                                for name, (r, w) in {"fold_mix_g16": (10, 8), "fold_mix_g32": (12, 8), "decay_mix": (8, 8),
                                                     "update_mix": (12, 4), "rescale_mix": (12, 12)}.items()}
+    # residency: the fold mix with the number of workgroups per compute unit bounded through unused LDS
+    out["residency_fold_mix_g16"] = {}
+    for block, groups, wgs in ((128, 1, 0), (128, 1, 12), (128, 1, 8), (128, 1, 6), (256, 1, 4), (128, 2, 4)):
+        lds = 0 if wgs == 0 else (160 * 1024 // wgs) & ~1023
+        fill(zero=False)
+        _, _, gbs = sustained("fold_mix_g16", block, launch_elems, lds=lds, groups=groups)
+        out["residency_fold_mix_g16"][f"{block}x{groups}@{wgs or 'all'}"] = round(gbs, 1)
     sweep = []
     for n in (1 << 20, 1 << 22, 1 << 23, 1 << 24, launch_elems, 1 << 26, 1 << 27, 1 << 28):
         n_, us, gbs = sustained("fold_mix_g16", 128, n)
         sweep.append({"elems": n_, "us_per_launch": round(us, 2), "GB/s": round(gbs, 1)})
-    xs = np.array([p["elems"] * 18.0 for p in sweep])
-    ts = np.array([p["us_per_launch"] for p in sweep])
+    xs = np.array([p["elems"] * 18.0 for p in sweep[:5]])      # up to one transformer block: beyond, long launches slow down
+    ts = np.array([p["us_per_launch"] for p in sweep[:5]])
     slope, icpt = np.polyfit(xs, ts, 1)
     out["launch_size_sweep"] = {"mode": "fold_mix_g16/128", "points": sweep,
-                                "fit": {"fixed_us_per_launch": round(float(icpt), 2),
-                                        "asymptotic_GB/s": round(1.0 / slope / 1e3, 1)}}
+                                "fit_up_to_one_block": {"fixed_us_per_launch": round(float(icpt), 2),
+                                                        "asymptotic_GB/s": round(1.0 / slope / 1e3, 1)}}
+    # the same fold mix on all-zero arrays: the contents matter
+    fill(zero=True)
+    out["all_zero_arrays"] = {f"fold_mix_g16/{b}": round(sustained("fold_mix_g16", b, launch_elems)[2], 1) for b in block_sizes}
+    lds = (160 * 1024 // 4) & ~1023
+    out["all_zero_arrays"]["fold_mix_g16/256x1@4"] = round(sustained("fold_mix_g16", 256, launch_elems, lds=lds)[2], 1)
     del synth
     return out
 
@@ -500,10 +535,17 @@ def main() -> int:
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,
                         "whole_model_bytes": w.P * w.grad_bytes},
     }
+    # hardware-counter traffic of the dominant kernel: taken by two rocprofv3 --pmc runs of this command and
+    # reduced by bench_traffic.py; quoted only while the library that was profiled is the one loaded now
     traffic_file = os.path.join(ROOT, "profiles", f"traffic_{w.name}.json" if opt != "sgdm" else f"traffic_{w.name}_sgdm.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as fh:
-            out["roofline"]["traffic"] = json.load(fh).get("bytes_per_launch")
+            tr = json.load(fh)
+        if tr.get("build_id") == binding.adama_build_id():
+            out["roofline"]["traffic"] = tr.get("bytes_per_launch")
+        else:
+            out["roofline"]["traffic_note"] = (f"{os.path.basename(traffic_file)} was measured on library build "
+                                               f"{tr.get('build_id')}, the loaded one is {binding.adama_build_id()}: not quoted")
     if args.cpu_budget > 0:
         out["cpu_baseline"] = cpu_baseline(w, args.cpu_budget, opt)
         out["cpu_baseline_all_cores"] = cpu_baseline_all_cores(w, args.cpu_budget / 2, opt)

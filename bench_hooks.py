@@ -3,8 +3,7 @@ synthetic tokens trained with (a) plain gradient accumulation + Adam, (b) AdamA 
 hooks (torch_hooks.AdamAccumulation) and (c) the same with the folds on a side stream, same model,
 same micro-batches.
 
-    python -m paper_2305_19982_amd.hook_demo [--layers 24] [--hidden 2048] [--heads 16] [--seq 1024]
-                                             [--micro-batch 4] [--N 8] [--steps 3]
+    python bench_hooks.py [--layers 24] [--hidden 2048] [--heads 16] [--seq 1024] [--micro-batch 4] [--N 8] [--steps 3]
 
 Prints one JSON line: step time and tokens/s of both, and the peak device memory each needed on top
 of parameters and optimizer state (Sec. 3.1: AdamA keeps one layer's gradients alive instead of the
@@ -16,12 +15,18 @@ from __future__ import annotations
 
 import argparse
 import json
+import os
+import sys
 import time
 
-import torch
-import torch.nn.functional as F
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
 
-from .torch_hooks import AdamAccumulation
+import torch  # noqa: E402
+import torch.nn.functional as F  # noqa: E402
+
+from paper_2305_19982_amd.torch_hooks import AdamAccumulation  # noqa: E402
 
 
 class Block(torch.nn.Module):

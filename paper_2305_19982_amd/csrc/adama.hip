@@ -49,17 +49,30 @@ constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 constexpr uint64_t kBigLaunchElems = 1u << 20;           // "big" launches: at least this many elements
 constexpr uint64_t kHugeLaunchElems = 3u << 25;          // "huge" launches: at least 100.7 M elements
+constexpr uint64_t kBoundedLaunchElems = 1u << 23;       // a policy's residency bound applies from this launch length on
 
-// Workgroup shape per op (index = Op) for small, big and huge launches.  Measured per op, as alternating
-// processes on one box, on whole transformer blocks (12.6 M .. 315 M elements per launch) and whole-state
-// lists.  The folds and the decay stream best through many small workgroups (128 threads x 1 group =
-// 512-element chunks: +0.9 % on 30 M-element launches over 256 x 1, +2 % over 256 x 2, +3.5 % over
-// 256 x 4; a CU refills at a finer grain and the grid's tail is shorter), except on launches beyond
-// about 100 M elements, where 256 x 4 is 0.4 % ahead.  Everything that ends in the update does best
-// with 256 x 1 (128 x 1 is 3 % slower there, 256 x 4 is 8 % slower: three read streams and long
-// dependent arithmetic).  The single-moment SGD ops move fewer bytes per element and need two groups
-// per thread to keep enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds, 128 x 2
-// for decay (+5 %) and update (+2 %).  Launches under 2^20 elements are latency-bound and use 256 x 1.
+// Launch policy per op (index = Op) for small, big and huge launches: threads per workgroup, 16-byte groups
+// per thread, and how many workgroups of the launch a compute unit may hold at once (0: no bound).
+// Measured per op on MI355X, in one process or as alternating processes on one box, on whole transformer
+// blocks (12.6 M .. 315 M elements per launch) and whole-state lists, with realistic array contents
+// (all-zero arrays stream 1..3 % faster and respond differently to every knob below, so they are no guide):
+//  * the folds and the decay stream best through many small workgroups (128 threads x 1 group =
+//    512-element chunks: +0.9 % on 30 M-element launches over 256 x 1, +2 % over 256 x 2, +3.5 % over
+//    256 x 4; a compute unit refills at a finer grain and the grid's tail is shorter), except on launches
+//    beyond about 100 M elements, where 256 x 4 is 0.4 % ahead;
+//  * the decay (as many bytes written as read) does best with 128 x 2, in launches of at most 2^26
+//    elements (+4 % on the GPT-2-shaped state over 80-tensor launches of 205 M elements);
+//  * the plain update does best with 256 x 1 (128 x 1 is 3 % slower there, 256 x 4 is 8 % slower: three
+//    read streams and long dependent arithmetic); the fused last fold with 128 x 1 (+0.9 % over 256 x 1);
+//  * the single-moment SGD ops move fewer bytes per element and need two groups per thread to keep
+//    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds, 128 x 2 for decay (+5 %)
+//    and update (+2 %);
+//  * bounding how many workgroups a compute unit holds (fewer requests in flight) changes the folds, the
+//    decay and the update by less than 1 % either way up to the point where the launch becomes
+//    latency-bound and falls off a cliff, so they run unbounded.  The data-parallel rescale, which writes
+//    three streams, gains 7 % with 4 workgroups of 128 x 2 per compute unit (launches under 2^23 elements,
+//    which need every slot to ramp up, stay unbounded);
+//  * launches under 2^20 elements are latency-bound and use 256 x 1.
 struct Policy {
     Shape small, big, huge;
     uint64_t max_launch_elems;   // a list is cut so that no launch of this op exceeds this many elements (0: no such cut)
@@ -70,8 +83,8 @@ struct Policy {
     /* fold              */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
     /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
     /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
-    /* fold_last_apply   */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
-    /* rescale_apply     */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
+    /* fold_last_apply   */ {{256, 1}, {128, 1}, {128, 1}, 0},                          \
+    /* rescale_apply     */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                    \
     /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
     /* sgd fold          */ {{256, 1}, {256, 2}, {256, 2}, 0},                          \
     /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
@@ -92,15 +105,14 @@ Shape launch_shape_for(int op, uint64_t elems)
 {
     const int cls = elems >= kHugeLaunchElems ? 2 : elems >= kBigLaunchElems ? 1 : 0;
     Shape s = cls == 2 ? kPolicy[op].huge : cls == 1 ? kPolicy[op].big : kPolicy[op].small;
+    if (elems < kBoundedLaunchElems) s.wgs = 0;
     if (g_residency_override_set && g_residency_override[op][cls] >= 0) s.wgs = g_residency_override[op][cls];
     return s;
 }
 
-// A compute unit of this chip has 160 KiB of LDS.  The kernels use none of it; a launch asks for an
+// A compute unit of this chip has 160 KiB of LDS.  The kernels use none of it; a launch may ask for an
 // (unused) share of it per workgroup only to bound how many of its workgroups a compute unit holds at
-// once, which bounds the number of memory requests in flight.  Measured: a streaming kernel at full
-// residency (32 wavefronts per compute unit) delivers 3..5 % less than one held to 8..16 wavefronts;
-// with too many requests queued the memory system reorders across too wide an address window.
+// once, which bounds the number of memory requests in flight (see the launch policy for where that pays).
 constexpr uint32_t kLdsPerComputeUnit = 160u * 1024u;
 uint32_t residency_lds_bytes(int wgs_per_cu)
 {

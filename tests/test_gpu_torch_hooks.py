@@ -233,7 +233,7 @@ def test_transformer_demo_saves_the_gradient_memory():
     memory is lower by most of the whole-model gradient size."""
     import argparse
 
-    from paper_2305_19982_amd import hook_demo
+    import bench_hooks as hook_demo
 
     args = argparse.Namespace(layers=4, hidden=512, heads=8, vocab=4000, seq=256, micro_batch=2, N=4, steps=2)
     out = hook_demo.compare(args)

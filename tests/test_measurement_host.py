@@ -25,7 +25,7 @@ def _write(path, counter, rows):
 
 
 def test_traffic_summary_scales_by_the_calibration_copy(tmp_path):
-    from paper_2305_19982_amd import traffic
+    import bench_traffic as traffic
 
     f, w = str(tmp_path / "f.csv"), str(tmp_path / "w.csv")
     # the fetch counter reads half of the real KiB (as on MI355X), the write counter the real KiB
@@ -39,7 +39,7 @@ def test_traffic_summary_scales_by_the_calibration_copy(tmp_path):
 
 
 def test_traffic_summary_refuses_ambiguous_input(tmp_path):
-    from paper_2305_19982_amd import traffic
+    import bench_traffic as traffic
 
     f, w = str(tmp_path / "f.csv"), str(tmp_path / "w.csv")
     _write(f, "FETCH_SIZE", [(COPY, 1.0), (COPY, 1.0), (FOLD, 1.0)])
