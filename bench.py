@@ -280,6 +280,12 @@ def main() -> int:
     ap.add_argument("--stream-probe", action="store_true",
                     help="instead of the benchmark: measure what the memory system delivers for the read : write mixes "
                          "of the path's kernels (no optimizer arithmetic) and print that as one JSON line")
+    ap.add_argument("--fold-streams", type=int, default=1,
+                    help="also time the same mini-batch with the folds of different layers spread over this many streams "
+                         "(layer l on stream l mod K; pays on launch-bound workloads only); reported as overlapped_folds")
+    ap.add_argument("--library", default=None,
+                    help="run a variant build of the library (python -m paper_2305_19982_amd.build --out ...) instead "
+                         "of the package's own, for A/B measurements; the line's library_build then reads \"variant\"")
     ap.add_argument("--no-torch-ops", action="store_true",
                     help="skip the context figure for the same fold written as stock PyTorch tensor ops")
     args = ap.parse_args()
@@ -298,6 +304,8 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         return 1
+    if args.library:
+        binding.use_library(args.library)
     if args.stream_probe:
         print(json.dumps({"stream_probe": stream_probe(), "peak_GB/s": HBM_PEAK_GBS}), flush=True)
         return 0
@@ -473,6 +481,23 @@ def main() -> int:
                  "params_per_s": round(w.P / (fused_ms * 1e-3), 1),
                  "note": "same results bit for bit; the fold_first / fold_last_apply entry points at the edges"}
 
+    # ---- the same mini-batch with the folds of different layers on K streams (ends and starts of launches overlap) ----
+    overlapped = None
+    if args.fold_streams > 1:
+        hb.use_fold_streams(args.fold_streams)
+        one_step(False)
+        hb.synchronize()
+        t4 = time.perf_counter()
+        for _ in range(args.steps):
+            one_step(False)
+        hb.synchronize()
+        ov_ms = (time.perf_counter() - t4) / args.steps * 1e3
+        hb.use_fold_streams(1)
+        overlapped = {"streams": args.fold_streams, "ms_per_step": round(ov_ms, 3),
+                      "value": round(algorithmic_bytes_per_step(w, opt) / (ov_ms * 1e-3) / 1e9, 1), "unit": "GB/s",
+                      "note": "layer l folded on stream l mod K; same results bit for bit; each stream would own a gradient "
+                              "buffer in the single-buffer layout"}
+
     # ---- live per-launch timing of the dominant kernel, HIP events on the launch stream ----
     for _ in range(min(2, args.steps)):
         one_step(True)
@@ -530,6 +555,7 @@ def main() -> int:
         "kernel_classes": kernel_classes,
         "fused_edges": fused,
         "fold_sweep": graph_sweep,
+        "overlapped_folds": overlapped,
         "torch_ops_baseline": torch_ops,
         "grad_memory": {"resident_for_timing_bytes": hb.peak_grad_bytes,
                         "adama_peak_bytes_largest_layer": w.largest_layer_elems * w.grad_bytes,

@@ -53,10 +53,23 @@ class adama_sgdm_tensor(ctypes.Structure):
 
 
 _lib = None
+_path_override = None
 
 
 def library_path() -> str:
-    return _build.LIB
+    return _path_override or _build.LIB
+
+
+def use_library(path: str) -> None:
+    """Load this library file instead of the package's own build (a variant made by
+    `python -m paper_2305_19982_amd.build --out ...` for an A/B measurement).  It is taken as it is: no check
+    against the sources, no rebuild.  Must be called before the first call into the library."""
+    global _path_override
+    if _lib is not None:
+        raise RuntimeError("a library is already loaded")
+    if not os.path.exists(path):
+        raise FileNotFoundError(path)
+    _path_override = os.path.abspath(path)
 
 
 def _may_build_here() -> bool:
@@ -77,13 +90,13 @@ def load() -> ctypes.CDLL:
     global _lib
     if _lib is not None:
         return _lib
-    if _build.stale():
+    if _path_override is None and _build.stale():
         if not _may_build_here():
             raise RuntimeError(f"{_build.LIB} is missing or was built from other sources (library "
                                f"{_build.library_id()}, sources {_build.source_id()}); build it first: "
                                "python -c 'import __graft_entry__ as g; g.build()'")
         _build.build_libadama()
-    lib = ctypes.CDLL(_build.LIB)
+    lib = ctypes.CDLL(library_path())
     vp, sz, dbl, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_double, ctypes.c_int, ctypes.c_longlong
     lib.adama_begin_step.argtypes = [vp, vp, sz, dbl, dbl, vp]
     lib.adama_begin_step_multi.argtypes = [ctypes.POINTER(adama_state), i32, dbl, dbl, vp]

@@ -51,9 +51,27 @@ def stale() -> bool:
     return library_id() != source_id()
 
 
-def build_libadama(verbose: bool = False) -> str:
-    tmp = LIB + f".tmp{os.getpid()}"
-    cmd = ["hipcc", *HIPCC_FLAGS, f'-DADAMA_BUILD_ID="{source_id()}"', "-I", os.path.join(ROOT, "include"),
+OPS = ["decay", "fold", "apply", "fold_first", "fold_last_apply", "rescale_apply", "sgd_decay", "sgd_fold", "sgd_apply",
+       "sgd_fold_first", "sgd_fold_last_apply"]
+
+
+def policy_define(shape: str) -> str:
+    """-D option that gives every op's big and huge launches the workgroup shape "BLOCKxGROUPS" (e.g. "128x2"),
+    unbounded residency, the decay's launch-length limit kept: for A/B builds of the launch policy."""
+    block, groups = (int(x) for x in shape.lower().split("x"))
+    rows = ", ".join("{{256, 1, 0}, {%d, %d, 0}, {%d, %d, 0}, %s}" % (block, groups, block, groups,
+                                                                    "ADAMA_DECAY_LAUNCH_CAP" if op == "decay" else "0")
+                     for op in OPS)
+    return "-DADAMA_POLICY_TABLE={" + rows + "}"
+
+
+def build_libadama(verbose: bool = False, out: str | None = None, extra_flags: list | None = None) -> str:
+    """Builds the library next to this file, or a variant (other -D options) at `out`; a variant carries the
+    build id "variant" so that it is never mistaken for the library of the sources as they stand."""
+    target = out or LIB
+    tmp = target + f".tmp{os.getpid()}"
+    build_id = source_id() if not extra_flags and out is None else "variant"
+    cmd = ["hipcc", *HIPCC_FLAGS, *(extra_flags or []), f'-DADAMA_BUILD_ID="{build_id}"', "-I", os.path.join(ROOT, "include"),
            "-I", os.path.join(PKG, "csrc"), "-o", tmp, *SOURCES]
     if verbose:
         print(" ".join(cmd), flush=True)
@@ -64,9 +82,17 @@ def build_libadama(verbose: bool = False) -> str:
         raise RuntimeError("hipcc failed:\n" + err)
     if verbose and err.strip():
         print(err)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, target)
+    return target
 
 
 if __name__ == "__main__":
-    print(build_libadama(verbose=True))
+    import argparse
+
+    ap = argparse.ArgumentParser(description="Build libadama.so, or a variant for A/B measurements (bench_ab.py).")
+    ap.add_argument("--out", default=None, help="write the library here instead of next to the package")
+    ap.add_argument("--shape", default=None, help='give every op\'s big and huge launches this workgroup shape, e.g. "128x2"')
+    ap.add_argument("--define", action="append", default=[], help="extra NAME=VALUE preprocessor definition (repeatable)")
+    a = ap.parse_args()
+    flags = [f"-D{d}" for d in a.define] + ([policy_define(a.shape)] if a.shape else [])
+    print(build_libadama(verbose=True, out=a.out, extra_flags=flags))

@@ -45,12 +45,21 @@ class SimulatedBackward:
                                  step methods are then ignored and `momentum` is used for the decay.
     weight_decay, grad_scale : decoupled weight decay of the update and the factor applied to every
                    gradient read (1/loss_scale); the defaults select the plain calls.
+    fold_streams : number of HIP streams (default priority) the folds are spread over: layer l is produced
+                   and folded on stream l mod fold_streams, so that the end of one layer's fold overlaps the
+                   start of the next one's.  Folds of one layer stay on one stream, hence in order across
+                   micro-batches; the decay precedes and the update follows all of them through events.  Each
+                   stream owns a gradient buffer of the largest layer's size (stream order is then still the
+                   only synchronisation a buffer needs), so peak gradient memory is fold_streams layers
+                   instead of one.  Pays only where launches are short (launch-bound workloads: +2..8 %);
+                   long launches lose 3 % because concurrent kernels interleave their address streams.
     """
 
     def __init__(self, tensor_sizes: Sequence[int], layers: Sequence[Sequence[int]], gdtype: str,
                  device: str = "cuda:0", stream: torch.cuda.Stream | None = None, pack: str = "aligned",
                  grad_buffer: str = "layer", optimizer: str = "adam", momentum: float = 0.9,
-                 weight_decay: float = 0.0, grad_scale: float = 1.0, arena_stagger_bytes: int | None = None):
+                 weight_decay: float = 0.0, grad_scale: float = 1.0, arena_stagger_bytes: int | None = None,
+                 fold_streams: int = 1):
         if gdtype not in _GRAD_BYTES:
             raise ValueError(gdtype)
         if optimizer not in ("adam", "sgdm"):
@@ -61,6 +70,10 @@ class SimulatedBackward:
         self._opt = None if (weight_decay == 0.0 and grad_scale == 1.0) else binding.options(weight_decay, grad_scale)
         self.device = torch.device(device)
         self.stream = stream if stream is not None else torch.cuda.Stream(device=self.device)
+        if fold_streams < 1:
+            raise ValueError("fold_streams must be >= 1")
+        self.fold_streams = [self.stream] + [torch.cuda.Stream(device=self.device) for _ in range(fold_streams - 1)]
+        self._grad_buffer_mode = grad_buffer
         self.gdtype = gdtype
         self.gbytes = _GRAD_BYTES[gdtype]
         self.sizes = [int(n) for n in tensor_sizes]
@@ -95,15 +108,26 @@ class SimulatedBackward:
                 self.m, self.v, self.theta = (views[0], views[1], views[2]) if narena == 3 else (views[0], None, views[1])
         # ---- the one gradient buffer: layer-local offsets, reused by every layer ----
         self.grad_offset = [0] * len(self.sizes)             # element offset inside the buffer
+        galign = align_elems * 4 // self.gbytes if pack == "aligned" else 1
         largest = 0
-        o = 0
-        for idx in self.layers:
-            if grad_buffer == "layer":
+        if grad_buffer == "layer":
+            for idx in self.layers:
                 o = 0
+                for ti in idx:
+                    o = _round_up(o + self.sizes[ti], galign)
+                largest = max(largest, o)
+            largest = _round_up(largest, 64)                 # one such region per fold stream
+        o = 0
+        for li, idx in enumerate(self.layers):
+            if grad_buffer == "layer":
+                o = (li % fold_streams) * largest
             for ti in idx:
                 self.grad_offset[ti] = o
-                o = _round_up(o + self.sizes[ti], align_elems * 4 // self.gbytes if pack == "aligned" else 1)
-            largest = max(largest, o)
+                o = _round_up(o + self.sizes[ti], galign)
+            if grad_buffer != "layer":
+                largest = max(largest, o)
+        if grad_buffer == "layer":
+            largest *= fold_streams
         self.grad_buffer_elems = max(largest, 1)
         self.grad_buffer = torch.empty(self.grad_buffer_elems * self.gbytes, dtype=torch.uint8, device=self.device)
         # ---- descriptor lists, built once ----
@@ -146,6 +170,39 @@ class SimulatedBackward:
     def stream_handle(self) -> int:
         return self.stream.cuda_stream
 
+    def use_fold_streams(self, k: int) -> None:
+        """Change the number of fold streams between mini-batches.  Only with grad_buffer="model" (every layer has
+        its own gradient region): the single-buffer layout fixes one region per stream at construction."""
+        if self._grad_buffer_mode == "layer" and k != len(self.fold_streams):
+            raise RuntimeError('the number of fold streams of a grad_buffer="layer" harness is fixed at construction')
+        if k < 1:
+            raise ValueError("fold_streams must be >= 1")
+        self.synchronize()
+        self.fold_streams = (self.fold_streams + [torch.cuda.Stream(device=self.device)
+                                                  for _ in range(k - len(self.fold_streams))])[:k]
+
+    def layer_stream(self, li: int) -> torch.cuda.Stream:
+        """The stream layer li's gradients are produced and folded on."""
+        return self.fold_streams[li % len(self.fold_streams)]
+
+    def layer_stream_handle(self, li: int) -> int:
+        return self.layer_stream(li).cuda_stream
+
+    def _fan_out(self) -> None:
+        """The other fold streams wait for what the main stream has queued so far."""
+        if len(self.fold_streams) > 1:
+            ev = torch.cuda.Event()
+            ev.record(self.stream)
+            for s in self.fold_streams[1:]:
+                s.wait_event(ev)
+
+    def _fan_in(self) -> None:
+        """The main stream waits for what the other fold streams have queued so far."""
+        for s in self.fold_streams[1:]:
+            ev = torch.cuda.Event()
+            ev.record(s)
+            self.stream.wait_event(ev)
+
     def grad_ptr(self, ti: int) -> int:
         return self.grad_buffer.data_ptr() + self.gbytes * self.grad_offset[ti]
 
@@ -164,44 +221,44 @@ class SimulatedBackward:
             binding.adama_sgdm_begin_step_multi(self._sgdm_state, None, self.momentum, self.stream_handle)
         else:
             binding.adama_begin_step_multi(self._state_list, None, beta1, beta2, self.stream_handle)
+        self._fan_out()
 
     def fold_layer(self, li: int, N: int, beta1: float, beta2: float) -> None:
+        sh = self.layer_stream_handle(li)
         if self.optimizer == "sgdm":
-            binding.adama_sgdm_fold_multi(self._sgdm_lists[li], None, self.gdtype, N, self._opt, self.stream_handle)
+            binding.adama_sgdm_fold_multi(self._sgdm_lists[li], None, self.gdtype, N, self._opt, sh)
         elif self._opt is None:
-            binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self.stream_handle)
+            binding.adama_fold_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, sh)
         else:
-            binding.adama_fold_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt,
-                                         self.stream_handle)
+            binding.adama_fold_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt, sh)
 
     # ---- the same mini-batch with the decay and the update riding along with the edge folds ----
     def begin_step_fused(self) -> None:
         """t <- t+1 only: the decay is performed by fold_layer_first in micro-batch 0."""
         self.t += 1
+        self._fan_out()
 
     def fold_layer_first(self, li: int, N: int, beta1: float, beta2: float) -> None:
         """Micro-batch 0: decay + fold of layer li in one pass (Alg. 1's one-statement form)."""
+        sh = self.layer_stream_handle(li)
         if self.optimizer == "sgdm":
-            binding.adama_sgdm_fold_first_multi(self._sgdm_lists[li], None, self.gdtype, N, self.momentum, self._opt,
-                                                self.stream_handle)
+            binding.adama_sgdm_fold_first_multi(self._sgdm_lists[li], None, self.gdtype, N, self.momentum, self._opt, sh)
         elif self._opt is None:
-            binding.adama_fold_first_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2,
-                                           self.stream_handle)
+            binding.adama_fold_first_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, sh)
         else:
-            binding.adama_fold_first_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt,
-                                               self.stream_handle)
+            binding.adama_fold_first_opt_multi(self._fold_lists[li], None, self.gdtype, N, beta1, beta2, self._opt, sh)
 
     def fold_layer_last_apply(self, li: int, N: int, lr: float, eps: float, beta1: float, beta2: float) -> None:
         """Micro-batch N-1: fold + parameter update of layer li in one pass."""
+        sh = self.layer_stream_handle(li)
         if self.optimizer == "sgdm":
-            binding.adama_sgdm_fold_last_apply_multi(self._sgdm_lists[li], None, self.gdtype, N, lr, self._opt,
-                                                     self.stream_handle)
+            binding.adama_sgdm_fold_last_apply_multi(self._sgdm_lists[li], None, self.gdtype, N, lr, self._opt, sh)
         elif self._opt is None:
             binding.adama_fold_last_apply_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1, beta2,
-                                                self.t, self.stream_handle)
+                                                self.t, sh)
         else:
             binding.adama_fold_last_apply_opt_multi(self._update_lists[li], None, self.gdtype, N, lr, eps, beta1,
-                                                    beta2, self.t, self._opt, self.stream_handle)
+                                                    beta2, self.t, self._opt, sh)
 
     def mini_batch_fused(self, produce: Callable[[int, int], None], N: int, lr: float, eps: float, beta1: float,
                          beta2: float) -> None:
@@ -221,13 +278,15 @@ class SimulatedBackward:
                     self.fold_layer(li, N, beta1, beta2)
 
     def micro_batch(self, produce: Callable[[int], None], N: int, beta1: float, beta2: float) -> None:
-        """One backward pass: for each layer, last to first, produce(li) must enqueue on self.stream
-        the writes of that layer's gradients into the buffer; the layer is then folded."""
+        """One backward pass: for each layer, last to first, produce(li) must enqueue on
+        self.layer_stream(li) (self.stream unless fold_streams > 1) the writes of that layer's gradients
+        into the buffer; the layer is then folded."""
         for li in range(len(self.layers) - 1, -1, -1):
             produce(li)
             self.fold_layer(li, N, beta1, beta2)
 
     def apply(self, lr: float, eps: float, beta1: float, beta2: float) -> None:
+        self._fan_in()
         if self.optimizer == "sgdm":
             binding.adama_sgdm_apply_multi(self._sgdm_state, None, lr, self._opt, self.stream_handle)
         elif self._opt is None:
@@ -250,6 +309,8 @@ class SimulatedBackward:
         graph.replay().  libadama's entry points neither allocate nor synchronise and carry their tensor
         tables inside the kernel arguments, so they can be captured as they are.  The step counter is host
         state: capture sequences whose scalars do not depend on t (decay and folds), or re-capture per step."""
+        if len(self.fold_streams) > 1:
+            raise RuntimeError("capture() records one stream: use fold_streams=1")
         graph = torch.cuda.CUDAGraph()
         self.stream.synchronize()
         with torch.cuda.graph(graph, stream=self.stream):
@@ -257,4 +318,5 @@ class SimulatedBackward:
         return graph
 
     def synchronize(self) -> None:
-        self.stream.synchronize()
+        for s in self.fold_streams:
+            s.synchronize()

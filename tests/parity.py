@@ -91,7 +91,7 @@ class WorkloadRun:
 
     def __init__(self, w: configs.Workload, pack: str = "aligned", sampled: bool = False, device: str = "cuda:0",
                  fused: bool = False, optimizer: str = "adam", momentum: float = 0.9, weight_decay: float = 0.0,
-                 grad_scale: float = 1.0, shadow: bool = False):
+                 grad_scale: float = 1.0, shadow: bool = False, fold_streams: int = 1):
         from paper_2305_19982_amd.harness import SimulatedBackward
 
         self.w = w
@@ -102,7 +102,7 @@ class WorkloadRun:
         self.optimizer, self.momentum, self.weight_decay, self.grad_scale = optimizer, momentum, weight_decay, grad_scale
         self.hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, device=device, pack=pack,
                                     optimizer=optimizer, momentum=momentum, weight_decay=weight_decay,
-                                    grad_scale=grad_scale)
+                                    grad_scale=grad_scale, fold_streams=fold_streams)
         rng = np.random.default_rng(1234)
         self.slices = [slices_of(t.n, rng) if sampled else [(0, t.n)] for t in w.tensors]
         # The oracle is called as it stands; a sampled full-size run merely calls it from several host
@@ -121,7 +121,7 @@ class WorkloadRun:
         # repeated or misplaced.  (Adam, separate calls only.)
         self.shadow = None
         if shadow:
-            assert optimizer == "adam" and not fused and weight_decay == 0.0 and grad_scale == 1.0
+            assert optimizer == "adam" and not fused and weight_decay == 0.0 and grad_scale == 1.0 and fold_streams == 1
             import torch
 
             with torch.cuda.stream(self.hb.stream):
@@ -154,7 +154,7 @@ class WorkloadRun:
         w = self.w
         for ti in w.layers[li]:
             synth.fill_device(self.hb.grad_ptr(ti), w.grad_spec(step, micro, ti), w.gdtype, w.tensors[ti].n,
-                              self.hb.stream_handle)
+                              self.hb.layer_stream_handle(li))
 
     def oracle_fold_layer(self, step: int, micro: int, li: int) -> None:
         w = self.w

@@ -324,6 +324,28 @@ def test_reduced_workload_fused_parity(torch_cuda, name):
         _log(f"{w.name} [fused] step {step}: {stats}")
 
 
+@pytest.mark.parametrize("name,fused", [("c4", False), ("c3", True), ("c2", False)])
+def test_folds_spread_over_streams_give_the_same_bits(torch_cuda, name, fused):
+    """fold_streams > 1: layer l is produced and folded on stream l mod k with a gradient buffer per stream;
+    the arithmetic and its order per element are unchanged, so two and three streams give the single
+    stream's bits, and the oracle agrees; peak gradient memory is k layers."""
+    torch = torch_cuda
+    w = configs.reduced(name)
+    outs, peaks = [], []
+    for k in (1, 2, 3):
+        run = WorkloadRun(w, pack="tight", sampled=False, fused=fused, fold_streams=k)
+        for step in range(1, w.steps + 1):
+            stats = run.run_step(step, check_grad_bits=(k == 2 and step == 1))
+        _log(f"{w.name} fold_streams={k}: {stats}")
+        run.hb.synchronize()
+        outs.append([x.clone() for x in (run.hb.theta, run.hb.m, run.hb.v)])
+        peaks.append(run.hb.peak_grad_bytes)
+    for other in outs[1:]:
+        for a, b in zip(outs[0], other):
+            assert torch.equal(a, b)
+    assert peaks[0] < peaks[1] <= 2 * peaks[0] + 1024 and peaks[1] < peaks[2] <= 3 * peaks[0] + 2048
+
+
 # ---------------------------------------------------------------------------
 # Sec. 3.3: M simulated devices on one GPU == one device with N*M micro-batches
 # ---------------------------------------------------------------------------
