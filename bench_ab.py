@@ -14,7 +14,8 @@ and, last, one JSON line with all figures (GB/s of algorithmic bytes).
 
 Ops: fold (12-tensor launches, bf16), single (one 30.7 M-element tensor per launch), fold32 (fp32 gradients, 16-tensor
 BERT-Large-shaped launches of 12.6 M elements), fold_first, fold_last_apply, decay, apply, rescale (whole-state lists),
-sgd_fold, sgd_fold_last_apply, sgd_decay, sgd_apply.
+sgd_fold, sgd_fold_first, sgd_fold_last_apply, sgd_decay, sgd_apply.  A library built from an older revision of the sources
+(without adama_debug_set_residency) can be timed with --residency -1.
 """
 from __future__ import annotations
 
@@ -32,7 +33,7 @@ BLOCK12 = [1600, 1600, 7680000, 4800, 2560000, 1600, 1600, 1600, 10240000, 6400,
 BLOCK16 = [1024 * 1024, 1024] * 4 + [1024, 1024, 1024 * 4096, 4096, 4096 * 1024, 1024, 1024, 1024]    # a BERT-Large layer
 LAYERS = 48
 BYTES = {"fold": 18, "single": 18, "fold32": 20, "fold_first": 18, "fold_last_apply": 26, "decay": 16, "apply": 16,
-         "rescale": 24, "sgd_fold": 10, "sgd_fold_last_apply": 18, "sgd_decay": 8, "sgd_apply": 12}
+         "rescale": 24, "sgd_fold": 10, "sgd_fold_first": 10, "sgd_fold_last_apply": 18, "sgd_decay": 8, "sgd_apply": 12}
 
 
 def main() -> int:
@@ -106,10 +107,14 @@ def main() -> int:
         lib.adama_rescale_apply_multi.argtypes = [sl, i32, dbl, dbl, dbl, dbl, dbl, dbl, i64, vpt]
         lib.adama_sgdm_begin_step_multi.argtypes = [gl, i32, dbl, vpt]
         lib.adama_sgdm_fold_multi.argtypes = [gl, i32, i32, i32, vpt, vpt]
+        lib.adama_sgdm_fold_first_multi.argtypes = [gl, i32, i32, i32, dbl, vpt, vpt]
         lib.adama_sgdm_apply_multi.argtypes = [gl, i32, dbl, vpt, vpt]
         lib.adama_sgdm_fold_last_apply_multi.argtypes = [gl, i32, i32, i32, dbl, vpt, vpt]
-        lib.adama_debug_set_residency.argtypes = [i32, i32, i32]
-        lib.adama_debug_set_residency.restype = None
+        if hasattr(lib, "adama_debug_set_residency"):
+            lib.adama_debug_set_residency.argtypes = [i32, i32, i32]
+            lib.adama_debug_set_residency.restype = None
+        elif bounds != [-1]:
+            raise SystemExit(f"{path} has no adama_debug_set_residency: time it with --residency -1")
         return lib
 
     def timed(fn, reps: int = 3) -> float:
@@ -147,6 +152,8 @@ def main() -> int:
             fn, elems = (lambda: lib.adama_rescale_apply_multi(state_l, len(state_l), 1.0, 1.0, 1e-3, 1e-8, 0.9, 0.999, 3, sh)), P
         elif op == "sgd_fold":
             fn, elems = (lambda: [lib.adama_sgdm_fold_multi(sgd_l[li], 12, B.BF16, 16, None, sh) for li in back]), P
+        elif op == "sgd_fold_first":
+            fn, elems = (lambda: [lib.adama_sgdm_fold_first_multi(sgd_l[li], 12, B.BF16, 16, 0.9, None, sh) for li in back]), P
         elif op == "sgd_fold_last_apply":
             fn, elems = (lambda: [lib.adama_sgdm_fold_last_apply_multi(sgd_l[li], 12, B.BF16, 16, 0.05, None, sh) for li in back]), P
         elif op == "sgd_decay":
@@ -164,9 +171,10 @@ def main() -> int:
             for name, lib in handles.items():
                 row = []
                 for r in bounds:
-                    for o in range(11):
-                        for cls in (1, 2):
-                            lib.adama_debug_set_residency(o, cls, r)
+                    if hasattr(lib, "adama_debug_set_residency"):
+                        for o in range(11):
+                            for cls in (1, 2):
+                                lib.adama_debug_set_residency(o, cls, r)
                     gbs = run(lib, op)
                     key = f"{op}|{name}|r{r}"
                     results[key] = max(results.get(key, 0.0), round(gbs, 1))

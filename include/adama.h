@@ -258,7 +258,8 @@ int adama_max_tensors_per_launch(void);
  * elements: *block = threads per workgroup, *groups_per_thread = 4-element groups each thread moves per
  * array (one workgroup handles block * 4 * groups elements; both 0 for an unknown op);
  * *big_launch_elems = the launch length from which the op's large-launch shape is used;
- * *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal state loads, 4 = non-temporal stores.
+ * *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal state loads, 4 = non-temporal stores,
+ * 8 = those stores also carry the agent-scope bit (written through the L2 at once).
  * Any pointer may be NULL. */
 void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
                   unsigned long long *big_launch_elems, int *policy_bits);

@@ -14,7 +14,17 @@ from __future__ import annotations
 import ctypes
 import os
 
-from . import build as _build
+
+
+class _Build:
+    """The build module, imported at first use (so that `python -m paper_2305_19982_amd.build` finds it unloaded)."""
+
+    def __getattr__(self, name):
+        from . import build
+        return getattr(build, name)
+
+
+_build = _Build()
 
 F32, BF16, F16 = 0, 1, 2
 DTYPES = {"f32": F32, "bf16": BF16, "f16": F16, F32: F32, BF16: BF16, F16: F16}

@@ -44,6 +44,16 @@ adama_status fail(adama_status st, const char *fmt, ...)
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
+// The ops (bit = Op) whose streaming stores also carry the agent-scope bit: the gradient folds.  In-process
+// A/B on the GPT-2-shaped state, with / without: fold +0.5 %, fold with fp32 gradients +0.4 %, first fold
+// +1.7 %, SGD fold +0.6 %; decay -4.7 %, update -2.2 %, rescale -5 %, fused last fold -0.8 %.
+#ifndef ADAMA_SCOPED_STORE_OPS
+#define ADAMA_SCOPED_STORE_OPS ((1 << kFold) | (1 << kFoldFirst) | (1 << kSgdFold) | (1 << kSgdFoldFirst))
+#endif
+constexpr int cache_policy(int op)
+{
+    return kNtPolicy | ((ADAMA_STORE_SCOPE != 0 && ((ADAMA_SCOPED_STORE_OPS >> op) & 1)) ? kScopedStore : 0);
+}
 // One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
 // a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
@@ -175,9 +185,9 @@ void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
     static_assert(BLOCK % 64 == 0 && BLOCK <= kMaxBlock && U >= 1, "workgroup shape");
     const uint32_t lds = residency_lds_bytes(b.shape.wgs);
     if (b.tab.count == 1)
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, true>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, cache_policy(OpK), true>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
     else
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, kNtPolicy, false>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, cache_policy(OpK), false>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
 }
 
 // Picks the instantiation for the batch's shape, which is one of the op's three.
@@ -446,7 +456,7 @@ void adama_tuning(int op, unsigned long long launch_elems, int *block, int *grou
     if (block) *block = s.block;
     if (groups_per_thread) *groups_per_thread = s.u;
     if (big_launch_elems) *big_launch_elems = kBigLaunchElems;
-    if (policy_bits) *policy_bits = kNtPolicy;
+    if (policy_bits) *policy_bits = (op >= 0 && op < kNumOps) ? cache_policy(op) : 0;
 }
 
 void adama_debug_set_residency(int op, int size_class, int wgs_per_cu)

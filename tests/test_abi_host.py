@@ -298,7 +298,8 @@ def test_geometry_chunk_size_follows_launch_size(lib):
             t = binding.adama_tuning(op, n)
             assert t["block"] in (64, 128, 256) and 1 <= t["groups_per_thread"] <= 8
             assert binding.adama_launch_chunk(op, n) == t["block"] * 4 * t["groups_per_thread"]
-    assert binding.adama_tuning(99, 5)["block"] == 0
+            assert t["policy_bits"] & 7 == 7 and t["policy_bits"] < 16      # all streams non-temporal; bit 8 per op
+    assert binding.adama_tuning(99, 5)["block"] == 0 and binding.adama_tuning(99, 5)["policy_bits"] == 0
     # one launch past the upper threshold, misaligned start: every element once, in bounds
     n = (3 << 25) + 5
     entries = [(FAKE + (3 << 40) + 12, FAKE + 12, FAKE + (1 << 40) + 12, FAKE + (2 << 40) + 6, n)]
