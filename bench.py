@@ -245,6 +245,29 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
         fill(zero=False)
         _, _, gbs = sustained("fold_mix_g16", block, launch_elems, lds=lds, groups=groups)
         out["residency_fold_mix_g16"][f"{block}x{groups}@{wgs or 'all'}"] = round(gbs, 1)
+    # persistent grid: k workgroups of 128 threads per compute unit walk the chunks with a fixed stride
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    n_per = launch_elems - launch_elems % 512
+    slots_per = max(1, arena_elems // n_per)
+    out["persistent_grid_fold_mix_g16"] = {}
+    for k in (2, 3, 4, 6, 8, 16):
+        fill(zero=False)
+
+        def launch(r: int, k: int = k) -> None:
+            off = (r % slots_per) * n_per
+            gen.stream_probe_persistent("fold_mix_g16", 128, cus * k, g.data_ptr() + 4 * off, arrays[0].data_ptr() + 4 * off,
+                                        arrays[1].data_ptr() + 4 * off, arrays[2].data_ptr() + 4 * off, sink.data_ptr(), n_per, sh)
+        for r in range(slots_per):
+            launch(r)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for r in range(2 * slots_per):
+            launch(r)
+        e1.record(stream)
+        e1.synchronize()
+        out["persistent_grid_fold_mix_g16"][f"{k} workgroups per compute unit"] = round(
+            18 * n_per * 2 * slots_per / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
     sweep = []
     for n in (1 << 20, 1 << 22, 1 << 23, 1 << 24, launch_elems, 1 << 26, 1 << 27, 1 << 28):
         n_, us, gbs = sustained("fold_mix_g16", 128, n)
@@ -255,6 +278,37 @@ def stream_probe(block_sizes=(128, 256), launch_elems: int = 30_740_800, arena_e
     out["launch_size_sweep"] = {"mode": "fold_mix_g16/128", "points": sweep,
                                 "fit_up_to_one_block": {"fixed_us_per_launch": round(float(icpt), 2),
                                                         "asymptotic_GB/s": round(1.0 / slope / 1e3, 1)}}
+    # cache policy: the fold mix (16-bit gradient, 128 x 1) with each combination of the sc0 / sc1 / nt modifiers
+    fill(zero=False)
+    n_pol = launch_elems - launch_elems % 512
+    slots = max(1, arena_elems // n_pol)
+
+    def policy_rate(lp: str, sp: str, what: str) -> float:
+        def launch(r: int) -> None:
+            off = (r % slots) * n_pol
+            gen.cache_policy_probe(lp, sp, what, g.data_ptr() + 4 * off, arrays[0].data_ptr() + 4 * off,
+                                   arrays[1].data_ptr() + 4 * off, sink.data_ptr(), n_pol, sh)
+        for r in range(slots):
+            launch(r)
+        stream.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for r in range(2 * slots):
+            launch(r)
+        e1.record(stream)
+        e1.synchronize()
+        bytes_per = {"mix": 18, "read": 10, "write": 8}[what]
+        return round(bytes_per * n_pol * 2 * slots / (e0.elapsed_time(e1) * 1e-3) / 1e9, 1)
+
+    pol = list(gen.CACHE_POLICIES)
+    out["cache_policy"] = {
+        "note": "fold mix with written-out global loads / stores; '' = no modifier; GB/s",
+        "mix_loads_nt_stores": {sp: policy_rate("nt", sp, "mix") for sp in pol},
+        "mix_stores_sc1_nt_loads": {lp: policy_rate(lp, "sc1 nt", "mix") for lp in pol},
+        "mix_no_modifiers": policy_rate("", "", "mix"),
+        "reads_alone": {lp: policy_rate(lp, "", "read") for lp in pol},
+    }
+    out["cache_policy"]["writes_alone"] = {sp: policy_rate("", sp, "write") for sp in pol}
     # the same fold mix on all-zero arrays: the contents matter
     fill(zero=True)
     out["all_zero_arrays"] = {f"fold_mix_g16/{b}": round(sustained("fold_mix_g16", b, launch_elems)[2], 1) for b in block_sizes}
@@ -283,6 +337,10 @@ def main() -> int:
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
                          "(layer l on stream l mod K; pays on launch-bound workloads only); reported as overlapped_folds")
+    ap.add_argument("--placement-tries", type=int, default=6,
+                    help="placements of the state in HBM the harness may try before the run (untimed set-up; 1 = take "
+                         "the first): the same step runs 2..4 %% faster or slower depending on where the driver put the "
+                         "arrays; reported as arena_placement")
     ap.add_argument("--library", default=None,
                     help="run a variant build of the library (python -m paper_2305_19982_amd.build --out ...) instead "
                          "of the package's own, for A/B measurements; the line's library_build then reads \"variant\"")
@@ -314,7 +372,8 @@ def main() -> int:
     opt = args.optimizer
     hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model",
                            optimizer="sgdm" if opt == "sgdm" else "adam", momentum=MOMENTUM,
-                           weight_decay=WEIGHT_DECAY[opt])
+                           weight_decay=WEIGHT_DECAY[opt], placement_tries=args.placement_tries,
+                           placement_micro_batches=w.N)
     sh = hb.stream_handle
     # ---- resident inputs: theta0 and one micro-batch of gradients, every layer at its own address ----
     for t in w.tensors:
@@ -394,7 +453,10 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     ms_per_step = elapsed / args.steps * 1e3
-    per_step = sorted(a.elapsed_time(b) for a, b in zip(step_marks[:-1], step_marks[1:]))
+    in_order = [a.elapsed_time(b) for a, b in zip(step_marks[:-1], step_marks[1:])]
+    per_step = sorted(in_order)
+    # up to 16 evenly spaced steps in the order they ran: shows a drift over the timed region, if any
+    trace_ms = [round(in_order[(i * (len(in_order) - 1)) // 15 if len(in_order) > 16 else i], 3) for i in range(min(16, len(in_order)))]
     median_ms = per_step[len(per_step) // 2] if len(per_step) % 2 else 0.5 * (per_step[len(per_step) // 2 - 1] + per_step[len(per_step) // 2])
 
     # ---- the same mini-batch with fused edges (decay inside micro-batch 0's folds, update inside the last) ----
@@ -534,6 +596,8 @@ def main() -> int:
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 3),
         "ms_per_step_median": round(median_ms, 3),
+        "ms_per_step_trace": trace_ms,
+        "arena_placement": hb.placement,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

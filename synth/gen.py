@@ -133,6 +133,8 @@ def _device_lib():
         _device.synth_stream_probe_persistent.restype = ctypes.c_int
         _device.synth_stream_probe_persistent.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_uint] + [
             ctypes.c_void_p] * 5 + [ctypes.c_uint64, ctypes.c_void_p]
+        _device.synth_cache_policy_probe.restype = ctypes.c_int
+        _device.synth_cache_policy_probe.argtypes = [ctypes.c_int] * 3 + [ctypes.c_void_p] * 4 + [ctypes.c_uint64, ctypes.c_void_p]
         _device.synth_stream_probe_bytes.restype = ctypes.c_int
         _device.synth_stream_probe_bytes.argtypes = [ctypes.c_int]
     return _device
@@ -141,6 +143,21 @@ def _device_lib():
 # Traffic-mix probe (synth_device.hip): streams with the access mix of the optimizer's kernels, no arithmetic.
 PROBE_MODES = {"read_g16_m_v": 0, "write_m_v": 1, "fold_mix_g16": 2, "fold_mix_g32": 3, "decay_mix": 4,
                "update_mix": 5, "rescale_mix": 6, "read_3xf32": 7}
+
+
+CACHE_POLICIES = {"": 0, "nt": 1, "sc0": 2, "sc1": 3, "sc0 sc1": 4, "sc0 sc1 nt": 5, "sc0 nt": 6, "sc1 nt": 7}
+
+
+def cache_policy_probe(load_policy: str, store_policy: str, what: str, g: int, a0: int, a1: int, sink: int, n: int,
+                       stream: int) -> None:
+    """Enqueue one launch of the fold's access mix ("mix", 18 B/element), its reads ("read", 10) or its writes
+    ("write", 8) over n elements (a multiple of 512) with the given modifiers on the loads and on the stores."""
+    rc = _device_lib().synth_cache_policy_probe(CACHE_POLICIES[load_policy], CACHE_POLICIES[store_policy],
+                                                {"mix": 0, "read": 1, "write": 2}[what], ctypes.c_void_p(g),
+                                                ctypes.c_void_p(a0), ctypes.c_void_p(a1), ctypes.c_void_p(sink), n,
+                                                ctypes.c_void_p(stream))
+    if rc:
+        raise RuntimeError(f"synth_cache_policy_probe({load_policy!r}, {store_policy!r}, {what}, n={n}) failed ({rc})")
 
 
 def stream_probe_bytes(mode: str) -> int:
@@ -160,7 +177,7 @@ def stream_probe(mode: str, block: int, g: int, a0: int, a1: int, a2: int, sink:
 
 def stream_probe_persistent(mode: str, block: int, grid: int, g: int, a0: int, a1: int, a2: int, sink: int, n: int,
                             stream: int) -> None:
-    """The same streams from a persistent grid of `grid` workgroups with the next chunk's loads issued early."""
+    """The same streams from a persistent grid: workgroup w of `grid` takes chunks w, w + grid, ... of block*4 elements."""
     rc = _device_lib().synth_stream_probe_persistent(PROBE_MODES[mode], block, grid, ctypes.c_void_p(g),
                                                      ctypes.c_void_p(a0), ctypes.c_void_p(a1), ctypes.c_void_p(a2),
                                                      ctypes.c_void_p(sink), n, ctypes.c_void_p(stream))

@@ -59,6 +59,23 @@ extern "C" int synth_copy_device(void *dst, const void *src, uint64_t bytes, voi
 typedef uint32_t synth_u32x2 __attribute__((ext_vector_type(2)));
 #define SYNTH_GLOBAL __attribute__((address_space(1)))
 
+/* Four float32 values of magnitude about 3e-5 with hashed mantissas: what a store-only probe writes, so that
+   the lines it writes are no easier to move than a workload's (all-zero lines stream faster). */
+__device__ __forceinline__ synth_f32x4 synth_varied(uint32_t seed)
+{
+    uint32_t h = seed * 2654435761u;
+    h ^= h >> 15;
+    synth_f32x4 r;
+    r.x = __builtin_bit_cast(float, (h & 0x807fffffu) | 0x38000000u);
+    h *= 2246822519u;
+    r.y = __builtin_bit_cast(float, (h & 0x807fffffu) | 0x38000000u);
+    h ^= h >> 13;
+    r.z = __builtin_bit_cast(float, (h & 0x807fffffu) | 0x38000000u);
+    h *= 3266489917u;
+    r.w = __builtin_bit_cast(float, (h & 0x807fffffu) | 0x38000000u);
+    return r;
+}
+
 template <int BLOCK, int U, int G16, int G32, int RW, int RO, int WO>
 __global__ void __launch_bounds__(BLOCK) synth_stream_probe_kernel(const void *g, float *a0, float *a1, float *a2, float *sink)
 {
@@ -72,6 +89,7 @@ __global__ void __launch_bounds__(BLOCK) synth_stream_probe_kernel(const void *g
     for (int u = 0; u < U; ++u) {
         const uint32_t i = u * BLOCK + threadIdx.x;
         acc[u] = synth_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (G16 + G32 + RW + RO == 0) acc[u] = synth_varied((uint32_t)e0 + i);
         if (G16) {
             synth_u32x2 w = __builtin_nontemporal_load((const SYNTH_GLOBAL synth_u32x2 *)((const uint16_t *)g + e0) + i);
             acc[u].x += __builtin_bit_cast(float, w.x << 16);
@@ -203,6 +221,108 @@ extern "C" int synth_stream_probe_persistent(int mode, int block, unsigned grid,
     if (block == 64) return synth_stream_probe_persistent_launch<64>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
     if (block == 128) return synth_stream_probe_persistent_launch<128>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
     return synth_stream_probe_persistent_launch<256>(mode, grid, g, a0, a1, a2, sink, nchunks, s);
+}
+
+/* Cache-policy probe: the fold's access mix (read a 16-bit array and two float32 arrays, write the two
+   float32 arrays back; 18 B/element) or its read half or write half alone, with a chosen combination of the
+   documented sc0 / sc1 / nt modifiers on the global loads and on the global stores.  The compiler's builtins
+   reach only "" and "nt", so the memory instructions are written out: every operand is a vector register
+   (hardware-interlocked), the loads are waited for explicitly (the compiler does not count loads it cannot
+   see), and each store is followed by the one wait state a store of more than 8 bytes needs before its data
+   registers may be overwritten. */
+#define SYNTH_POLICY_CASES(OP, ...)                                                         \
+    if constexpr (P == 0) asm volatile(OP " %0, %1, off" __VA_ARGS__);                      \
+    if constexpr (P == 1) asm volatile(OP " %0, %1, off nt" __VA_ARGS__);                   \
+    if constexpr (P == 2) asm volatile(OP " %0, %1, off sc0" __VA_ARGS__);                  \
+    if constexpr (P == 3) asm volatile(OP " %0, %1, off sc1" __VA_ARGS__);                  \
+    if constexpr (P == 4) asm volatile(OP " %0, %1, off sc0 sc1" __VA_ARGS__);              \
+    if constexpr (P == 5) asm volatile(OP " %0, %1, off sc0 sc1 nt" __VA_ARGS__);           \
+    if constexpr (P == 6) asm volatile(OP " %0, %1, off sc0 nt" __VA_ARGS__);               \
+    if constexpr (P == 7) asm volatile(OP " %0, %1, off sc1 nt" __VA_ARGS__)
+
+template <int P> __device__ __forceinline__ synth_f32x4 synth_policy_ld16(const float *p)
+{
+    synth_f32x4 r;
+    SYNTH_POLICY_CASES("global_load_dwordx4", : "=v"(r) : "v"(p) : "memory");
+    return r;
+}
+template <int P> __device__ __forceinline__ synth_u32x2 synth_policy_ld8(const uint16_t *p)
+{
+    synth_u32x2 r;
+    SYNTH_POLICY_CASES("global_load_dwordx2", : "=v"(r) : "v"(p) : "memory");
+    return r;
+}
+template <int P> __device__ __forceinline__ void synth_policy_st16(float *p, synth_f32x4 x)
+{
+#define SYNTH_ST_CASE(N, MODS) if constexpr (P == N) asm volatile("global_store_dwordx4 %0, %1, off" MODS "\n\ts_nop 0" : : "v"(p), "v"(x) : "memory")
+    SYNTH_ST_CASE(0, ""); SYNTH_ST_CASE(1, " nt"); SYNTH_ST_CASE(2, " sc0"); SYNTH_ST_CASE(3, " sc1"); SYNTH_ST_CASE(4, " sc0 sc1");
+    SYNTH_ST_CASE(5, " sc0 sc1 nt"); SYNTH_ST_CASE(6, " sc0 nt"); SYNTH_ST_CASE(7, " sc1 nt");
+#undef SYNTH_ST_CASE
+}
+
+/* WHAT: 0 = the mix, 1 = the reads alone, 2 = the writes alone.  One workgroup of 128 threads per 512 elements. */
+template <int LP, int SP, int WHAT>
+__global__ void __launch_bounds__(128) synth_cache_policy_kernel(const uint16_t *g, float *a0, float *a1, float *sink)
+{
+    const uint64_t e = (uint64_t)blockIdx.x * 512 + threadIdx.x * 4;
+    synth_f32x4 x0 = {0.0f, 0.0f, 0.0f, 0.0f}, x1 = x0;
+    synth_u32x2 w = {0u, 0u};
+    if (WHAT == 2) {
+        x0 = synth_varied((uint32_t)e);
+        x1 = synth_varied((uint32_t)e + 1u);
+    }
+    if (WHAT != 2) {
+        w = synth_policy_ld8<LP>(g + e);
+        x0 = synth_policy_ld16<LP>(a0 + e);
+        x1 = synth_policy_ld16<LP>(a1 + e);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    synth_f32x4 gg;
+    gg.x = __builtin_bit_cast(float, w.x << 16);
+    gg.y = __builtin_bit_cast(float, w.x & 0xffff0000u);
+    gg.z = __builtin_bit_cast(float, w.y << 16);
+    gg.w = __builtin_bit_cast(float, w.y & 0xffff0000u);
+    const synth_f32x4 y0 = x0 + gg, y1 = x1 + gg;
+    if (WHAT != 1) {
+        synth_policy_st16<SP>(a0 + e, y0);
+        synth_policy_st16<SP>(a1 + e, y1);
+    } else {
+        const float keep = y0.x + y0.y + y0.z + y0.w + y1.x + y1.y + y1.z + y1.w;
+        if (keep == 12345.678f) *sink = keep;
+    }
+}
+
+template <int LP, int WHAT>
+static void synth_cache_policy_launch(int sp, unsigned grid, const uint16_t *g, float *a0, float *a1, float *sink, hipStream_t s)
+{
+#define SYNTH_SP(N) case N: hipLaunchKernelGGL((synth_cache_policy_kernel<LP, N, WHAT>), dim3(grid), dim3(128), 0, s, g, a0, a1, sink); break
+    switch (sp) { SYNTH_SP(0); SYNTH_SP(1); SYNTH_SP(2); SYNTH_SP(3); SYNTH_SP(4); SYNTH_SP(5); SYNTH_SP(6); SYNTH_SP(7); }
+#undef SYNTH_SP
+}
+
+/* Enqueue one cache-policy probe launch over the first n elements (a multiple of 512) of g (16-bit elements), a0
+   and a1 (float32), all 16-byte aligned device memory of at least n elements.  load_policy and store_policy:
+   0 none, 1 nt, 2 sc0, 3 sc1, 4 sc0 sc1, 5 sc0 sc1 nt, 6 sc0 nt, 7 sc1 nt.  what: 0 mix (18 B/element), 1 reads
+   alone (10), 2 writes alone (8).  Returns 0, 1 on a bad argument, 2 on a HIP error. */
+extern "C" int synth_cache_policy_probe(int load_policy, int store_policy, int what, const void *g, float *a0, float *a1,
+                                        float *sink, uint64_t n, void *stream)
+{
+    if (n == 0) return 0;
+    if (load_policy < 0 || load_policy > 7 || store_policy < 0 || store_policy > 7 || what < 0 || what > 2) return 1;
+    if (!g || !a0 || !a1 || !sink || n % 512 || n / 512 > 0x7FFFFFFFull) return 1;
+    if (((uintptr_t)g | (uintptr_t)a0 | (uintptr_t)a1) & 15) return 1;
+    const unsigned grid = (unsigned)(n / 512);
+    const uint16_t *gp = (const uint16_t *)g;
+    hipStream_t s = (hipStream_t)stream;
+#define SYNTH_LP(N)                                                                              \
+    case N:                                                                                      \
+        if (what == 0) synth_cache_policy_launch<N, 0>(store_policy, grid, gp, a0, a1, sink, s); \
+        else if (what == 1) synth_cache_policy_launch<N, 1>(store_policy, grid, gp, a0, a1, sink, s); \
+        else synth_cache_policy_launch<N, 2>(store_policy, grid, gp, a0, a1, sink, s);           \
+        break
+    switch (load_policy) { SYNTH_LP(0); SYNTH_LP(1); SYNTH_LP(2); SYNTH_LP(3); SYNTH_LP(4); SYNTH_LP(5); SYNTH_LP(6); SYNTH_LP(7); }
+#undef SYNTH_LP
+    return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 
 /* Bytes per element of a probe mode, 0 for an unknown mode. */

@@ -572,16 +572,27 @@ def test_concurrent_host_threads_on_their_own_streams(torch_cuda):
     check_close("threads", "v", results[0][1], rv)
 
 
-def test_arena_placement_does_not_change_results(torch_cuda):
-    """The harness can place theta, m, v in one slab with the arenas staggered against each other (a
-    knob for measuring how relative placement affects bandwidth); results are bit-identical."""
+@pytest.mark.parametrize("optimizer", ["adam", "sgdm"])
+def test_arena_placement_does_not_change_results(torch_cuda, optimizer):
+    """Where the state lives does not change the results: one slab with the arenas staggered against each other
+    (a knob for measuring how relative placement affects bandwidth), or the fastest of three placements the
+    harness tried (placement_tries: it times decay, folds and update on each candidate with scratch contents,
+    keeps the best and hands it over zeroed); bit-identical state after a mini-batch."""
     torch = torch_cuda
     from paper_2305_19982_amd.harness import SimulatedBackward
 
     w = configs.reduced("c3")
     outs = []
-    for stagger in (None, 0, 4096):
-        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, pack="tight", arena_stagger_bytes=stagger)
+    for stagger, tries in ((None, 1), (0, 1), (4096, 1), (None, 3), (4096, 2)):
+        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, pack="tight", arena_stagger_bytes=stagger,
+                               optimizer=optimizer, placement_tries=tries, placement_micro_batches=w.N)
+        hb.synchronize()
+        assert hb.placement["tries"] == tries and len(hb.placement["step_ms"]) == (tries if tries > 1 else 0)
+        assert 0 <= hb.placement["chosen"] < tries
+        if tries > 1:
+            assert hb.placement["step_ms"][hb.placement["chosen"]] == min(hb.placement["step_ms"])
+        for arena in (hb.theta, hb.m, hb.v):
+            assert arena is None or not bool(arena.any())            # handed over zeroed
         for t in w.tensors:
             synth.fill_device(hb.theta_ptr(t.index), w.theta_spec(t.index), "f32", t.n, hb.stream_handle)
 
@@ -591,9 +602,11 @@ def test_arena_placement_does_not_change_results(torch_cuda):
 
         hb.mini_batch(produce, w.N, w.lr, w.eps, w.beta1, w.beta2)
         hb.synchronize()
-        outs.append([torch.cat([hb.tensor_view(k, t.index) for t in w.tensors]).clone() for k in ("theta", "m", "v")])
+        kinds = ("theta", "m", "v") if optimizer == "adam" else ("theta", "b")
+        outs.append([torch.cat([hb.tensor_view(k, t.index) for t in w.tensors]).clone() for k in kinds])
         if stagger is not None:
-            assert (hb.v.data_ptr() - hb.m.data_ptr()) % (1 << 21) == stagger
+            other = hb.v if optimizer == "adam" else hb.theta
+            assert (other.data_ptr() - hb.m.data_ptr()) % (1 << 21) == stagger
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
