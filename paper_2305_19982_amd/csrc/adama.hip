@@ -50,16 +50,23 @@ constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
 #ifndef ADAMA_SCOPED_STORE_OPS
 #define ADAMA_SCOPED_STORE_OPS ((1 << kFold) | (1 << kFoldFirst) | (1 << kSgdFold) | (1 << kSgdFoldFirst))
 #endif
-constexpr int cache_policy(int op)
+// Only launches of at least 2^23 elements carry it: a store with the scope bit has to reach memory before its
+// kernel can end, which adds about 2 us to a launch and is paid back by the faster streaming of a long one
+// only (a launch of 20 small tensors replayed from a HIP graph: 3.8 us without, 4.35 us with).
+constexpr int cache_policy(int op, bool long_launch)
 {
-    return kNtPolicy | ((ADAMA_STORE_SCOPE != 0 && ((ADAMA_SCOPED_STORE_OPS >> op) & 1)) ? kScopedStore : 0);
+    return kNtPolicy |
+           ((ADAMA_STORE_SCOPE != 0 && long_launch && ((ADAMA_SCOPED_STORE_OPS >> op) & 1)) ? kScopedStore : 0);
 }
 // One workgroup per chunk (grid == number of chunks): the hardware dispatcher refills a CU as soon as
 // a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 constexpr uint64_t kBigLaunchElems = 1u << 20;           // "big" launches: at least this many elements
 constexpr uint64_t kHugeLaunchElems = 3u << 25;          // "huge" launches: at least 100.7 M elements
-constexpr uint64_t kBoundedLaunchElems = 1u << 23;       // a policy's residency bound applies from this launch length on
+#ifndef ADAMA_LONG_LAUNCH_ELEMS
+#define ADAMA_LONG_LAUNCH_ELEMS (1u << 23)
+#endif
+constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;   // a policy's residency bound and store scope apply from this launch length on
 
 // Launch policy per op (index = Op) for small, big and huge launches: threads per workgroup, 16-byte groups
 // per thread, and how many workgroups of the launch a compute unit may hold at once (0: no bound).
@@ -77,11 +84,13 @@ constexpr uint64_t kBoundedLaunchElems = 1u << 23;       // a policy's residency
 //  * the single-moment SGD ops move fewer bytes per element and need two groups per thread to keep
 //    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds, 128 x 2 for decay (+5 %)
 //    and update (+2 %);
-//  * bounding how many workgroups a compute unit holds (fewer requests in flight) changes the folds, the
-//    decay and the update by less than 1 % either way up to the point where the launch becomes
-//    latency-bound and falls off a cliff, so they run unbounded.  The data-parallel rescale, which writes
-//    three streams, gains 7 % with 4 workgroups of 128 x 2 per compute unit (launches under 2^23 elements,
-//    which need every slot to ramp up, stay unbounded);
+//  * bounding how many workgroups a compute unit holds (fewer requests in flight) changes the decay, the
+//    update and the edge folds by less than 1 % either way up to the point where the launch becomes
+//    latency-bound and falls off a cliff, so they run unbounded.  The plain fold, whose stores carry the
+//    agent-scope bit, gains 0.7..1.0 % with bf16 gradients and 1.7 % with fp32 gradients at 13 workgroups of
+//    128 x 1 (same in three processes; without the scope bit it was flat).  The data-parallel rescale, which
+//    writes three streams, gains 7 % with 4 workgroups of 128 x 2.  Launches under 2^23 elements, which need
+//    every slot to ramp up, stay unbounded;
 //  * launches under 2^20 elements are latency-bound and use 256 x 1.
 struct Policy {
     Shape small, big, huge;
@@ -90,7 +99,7 @@ struct Policy {
 #ifndef ADAMA_POLICY_TABLE
 #define ADAMA_POLICY_TABLE {                                                            \
     /* decay             */ {{256, 1}, {128, 2}, {128, 2}, ADAMA_DECAY_LAUNCH_CAP},     \
-    /* fold              */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
+    /* fold              */ {{256, 1}, {128, 1, 13}, {256, 4}, 0},                          \
     /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
     /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
     /* fold_last_apply   */ {{256, 1}, {128, 1}, {128, 1}, 0},                          \
@@ -111,9 +120,12 @@ constexpr Policy kPolicy[kNumOps] = ADAMA_POLICY_TABLE;
 int g_residency_override[kNumOps][3];
 bool g_residency_override_set = false;
 
+// Size class of a launch: 0 small (latency-bound), 1 big, 2 huge.
+int launch_class(uint64_t elems) { return elems >= kHugeLaunchElems ? 2 : elems >= kBigLaunchElems ? 1 : 0; }
+
 Shape launch_shape_for(int op, uint64_t elems)
 {
-    const int cls = elems >= kHugeLaunchElems ? 2 : elems >= kBigLaunchElems ? 1 : 0;
+    const int cls = launch_class(elems);
     Shape s = cls == 2 ? kPolicy[op].huge : cls == 1 ? kPolicy[op].big : kPolicy[op].small;
     if (elems < kBoundedLaunchElems) s.wgs = 0;
     if (g_residency_override_set && g_residency_override[op][cls] >= 0) s.wgs = g_residency_override[op][cls];
@@ -137,6 +149,8 @@ uint32_t grad_bytes(int op, int gdt) { return !op_has_grad(op) ? 0u : gdt == kF3
 struct Batch {
     Table<kMaxTensors> tab;
     Shape shape;           // workgroup size and groups per thread
+    int size_class;        // 0 small, 1 big, 2 huge: which of the op's three shapes `shape` is
+    bool long_launch;      // at least kBoundedLaunchElems elements: residency bound and store scope apply
     uint32_t total;        // chunks
 };
 
@@ -158,6 +172,8 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
             ++k;
         }
         b.shape = launch_shape_for(op, elems);
+        b.size_class = launch_class(elems);
+        b.long_launch = elems >= kBoundedLaunchElems;
         const uint32_t chunk = chunk_elems(b.shape);
         uint64_t start = 0;
         for (int j = 0; j < k; ++j) {
@@ -179,15 +195,15 @@ adama_status for_each_batch(int op, const Desc *descs, int count, Emit &&emit)
     return ADAMA_OK;
 }
 
-template <int OpK, int GT, int BLOCK, int U>
+template <int OpK, int GT, int BLOCK, int U, int NT>
 void launch_one(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
     static_assert(BLOCK % 64 == 0 && BLOCK <= kMaxBlock && U >= 1, "workgroup shape");
     const uint32_t lds = residency_lds_bytes(b.shape.wgs);
     if (b.tab.count == 1)
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, cache_policy(OpK), true>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, NT, true>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
     else
-        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, cache_policy(OpK), false>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
+        hipLaunchKernelGGL((multi_tensor_kernel<OpK, GT, BLOCK, U, NT, false>), dim3(b.total), dim3(BLOCK), lds, stream, b.tab, sc);
 }
 
 // Picks the instantiation for the batch's shape, which is one of the op's three.
@@ -195,9 +211,10 @@ template <int OpK, int GT>
 void launch_u(const Batch &b, const Scalars &sc, hipStream_t stream)
 {
     constexpr Policy P = kPolicy[OpK];
-    if (same_shape(b.shape, P.small)) launch_one<OpK, GT, P.small.block, P.small.u>(b, sc, stream);
-    else if (same_shape(b.shape, P.big)) launch_one<OpK, GT, P.big.block, P.big.u>(b, sc, stream);
-    else launch_one<OpK, GT, P.huge.block, P.huge.u>(b, sc, stream);
+    if (b.size_class == 0) launch_one<OpK, GT, P.small.block, P.small.u, cache_policy(OpK, false)>(b, sc, stream);
+    else if (b.size_class == 2) launch_one<OpK, GT, P.huge.block, P.huge.u, cache_policy(OpK, true)>(b, sc, stream);
+    else if (b.long_launch) launch_one<OpK, GT, P.big.block, P.big.u, cache_policy(OpK, true)>(b, sc, stream);
+    else launch_one<OpK, GT, P.big.block, P.big.u, cache_policy(OpK, false)>(b, sc, stream);
 }
 
 template <int OpK>
@@ -456,7 +473,7 @@ void adama_tuning(int op, unsigned long long launch_elems, int *block, int *grou
     if (block) *block = s.block;
     if (groups_per_thread) *groups_per_thread = s.u;
     if (big_launch_elems) *big_launch_elems = kBigLaunchElems;
-    if (policy_bits) *policy_bits = (op >= 0 && op < kNumOps) ? cache_policy(op) : 0;
+    if (policy_bits) *policy_bits = (op >= 0 && op < kNumOps) ? cache_policy(op, launch_elems >= kBoundedLaunchElems) : 0;
 }
 
 void adama_debug_set_residency(int op, int size_class, int wgs_per_cu)
