@@ -337,7 +337,7 @@ def main() -> int:
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
                          "(layer l on stream l mod K; pays on launch-bound workloads only); reported as overlapped_folds")
-    ap.add_argument("--placement-tries", type=int, default=6,
+    ap.add_argument("--placement-tries", type=int, default=10,
                     help="placements of the state in HBM the harness may try before the run (untimed set-up; 1 = take "
                          "the first): the same step runs 2..4 %% faster or slower depending on where the driver put the "
                          "arrays; reported as arena_placement")
