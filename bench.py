@@ -12,6 +12,16 @@ libadama launches.  Prints ONE JSON line.
 --optimizer selects the same pass for a variant: "adamw" (decoupled weight decay 0.01 in the update,
 same kernels and bytes) or "sgdm" (SGD with momentum 0.9 accumulated the same way: one moment, so
 8 B decay + N x (8 + gradient) B folds + 12 B update per parameter).  The default is the paper's AdamA.
+
+Before the warm-up the harness places the state: what HBM delivers depends on where the driver put the
+arrays (2..4 % of the step), so it times up to --placement-tries candidate allocations and keeps the
+fastest; every candidate's estimated step time is reported as arena_placement (1 = take the first).
+
+Other modes: --graph (a micro-batch's sweep eager and as a HIP graph), --fold-streams K (folds spread
+over K streams, reported beside the one-stream figure), --library FILE (a variant build, for A/B),
+--calibration-copy (a known-size copy kernel for scaling hardware counters), --stream-probe (instead of
+the benchmark: what the memory system delivers for the path's read : write mixes, cache policies,
+residency bounds, a persistent grid and a sweep of launch sizes, with no optimizer arithmetic).
 """
 from __future__ import annotations
 
@@ -336,7 +346,7 @@ def main() -> int:
                          "of the path's kernels (no optimizer arithmetic) and print that as one JSON line")
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
-                         "(layer l on stream l mod K; pays on launch-bound workloads only); reported as overlapped_folds")
+                         "(layer l on stream l mod K; measured: no robust gain); reported as overlapped_folds")
     ap.add_argument("--placement-tries", type=int, default=10,
                     help="placements of the state in HBM the harness may try before the run (untimed set-up; 1 = take "
                          "the first): the same step runs 2..4 %% faster or slower depending on where the driver put the "
