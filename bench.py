@@ -13,9 +13,10 @@ libadama launches.  Prints ONE JSON line.
 same kernels and bytes) or "sgdm" (SGD with momentum 0.9 accumulated the same way: one moment, so
 8 B decay + N x (8 + gradient) B folds + 12 B update per parameter).  The default is the paper's AdamA.
 
-Before the warm-up the harness places the state: what HBM delivers depends on where the driver put the
-arrays (2..4 % of the step), so it times up to --placement-tries candidate allocations and keeps the
-fastest; every candidate's estimated step time is reported as arena_placement (1 = take the first).
+Before the warm-up the harness places the state: what HBM delivers depends on where the arrays lie (the
+distance between the arenas, the physical pages behind them: 2..6 % of the step), so it times
+--placement-tries allocations x --pitch-tries distances and keeps the fastest; every candidate's
+estimated step time is reported as arena_placement (1 and 1 = take the first).
 
 Other modes: --graph (a micro-batch's sweep eager and as a HIP graph), --fold-streams K (folds spread
 over K streams, reported beside the one-stream figure), --library FILE (a variant build, for A/B),
@@ -347,10 +348,15 @@ def main() -> int:
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
                          "(layer l on stream l mod K; measured: no robust gain); reported as overlapped_folds")
-    ap.add_argument("--placement-tries", type=int, default=10,
-                    help="placements of the state in HBM the harness may try before the run (untimed set-up; 1 = take "
-                         "the first): the same step runs 2..4 %% faster or slower depending on where the driver put the "
-                         "arrays; reported as arena_placement")
+    ap.add_argument("--placement-tries", type=int, default=3,
+                    help="allocations of the state the harness may try before the run (untimed set-up; needs room for a "
+                         "second copy): the same step runs 2..6 %% faster or slower depending on where the arrays lie; "
+                         "every candidate's estimated step time is reported as arena_placement")
+    ap.add_argument("--arena-layout", default="slab", choices=["slab", "separate"],
+                    help="how the harness lays out theta, m, v: one allocation with the arenas a multiple of 2 MiB apart "
+                         "(default), or one allocation per arena")
+    ap.add_argument("--pitch-tries", type=int, default=8,
+                    help="distances between the arenas of a slab the harness may try (2 MiB apart; no extra memory)")
     ap.add_argument("--library", default=None,
                     help="run a variant build of the library (python -m paper_2305_19982_amd.build --out ...) instead "
                          "of the package's own, for A/B measurements; the line's library_build then reads \"variant\"")
@@ -382,7 +388,9 @@ def main() -> int:
     opt = args.optimizer
     hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, grad_buffer="model",
                            optimizer="sgdm" if opt == "sgdm" else "adam", momentum=MOMENTUM,
-                           weight_decay=WEIGHT_DECAY[opt], placement_tries=args.placement_tries,
+                           weight_decay=WEIGHT_DECAY[opt], arena_layout=args.arena_layout,
+                           placement_tries=args.placement_tries,
+                           pitch_tries=args.pitch_tries if args.arena_layout == "slab" else 1,
                            placement_micro_batches=w.N)
     sh = hb.stream_handle
     # ---- resident inputs: theta0 and one micro-batch of gradients, every layer at its own address ----

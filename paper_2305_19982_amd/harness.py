@@ -45,16 +45,26 @@ class SimulatedBackward:
                                  step methods are then ignored and `momentum` is used for the decay.
     weight_decay, grad_scale : decoupled weight decay of the update and the factor applied to every
                    gradient read (1/loss_scale); the defaults select the plain calls.
-    placement_tries : how many placements of the state in HBM to try before settling (default 1: take the first).
-                   What the memory system delivers for arrays streamed together depends on where the driver
-                   happened to put them (their physical pages decide which channels and banks the streams meet
-                   on): on MI355X the same step runs 2..4 % faster or slower from one allocation of the same
-                   arenas to the next, and stays so for as long as the allocation lives.  With k > 1 the harness
-                   allocates up to k candidates (the best so far held, so that each candidate lands elsewhere),
-                   times decay + folds + update on each with contents like a workload's, keeps the fastest and
-                   zeroes it.  Costs well under a second and twice the state's memory while it runs; stops
-                   early when a second copy does not fit.  `placement` records what was measured.
+    arena_layout : "slab" (default): theta, m, v in one allocation, arena k starting k * pitch bytes after the
+                   first, the pitch a multiple of 2 MiB; "separate": one allocation per arena, wherever the
+                   allocator puts them.
+    Placement.     What the memory system delivers for arrays that are streamed in lock step depends on which
+                   channels and banks their addresses hash to, i.e. on the distance between the arenas and on
+                   the physical pages the driver handed out: on MI355X the same mini-batch runs 2..6 % faster
+                   or slower from one placement to the next (the fold of GPT-2-XL blocks: 6.37..6.61 TB/s over
+                   pitches of one slab that differ by 2 MiB) and stays so for as long as the placement lives.
+                   No rule for the distance held up across allocations, so the harness measures:
+    pitch_tries  : how many pitches to try inside a slab (the smallest that fits, then 2 MiB more each time;
+                   default 1), or the list of extras to try, in 2 MiB units (e.g. [0, 1, 64, 65]).  Costs no
+                   extra memory beyond the largest extra, so it works for a state that fills the device.
+    placement_tries : how many allocations to try (default 1).  Each further one needs room for a second copy
+                   of the state (the best so far is held, so that the next lands elsewhere); stops early when
+                   there is none.  Every candidate (allocation x pitch) is timed on decay + N fold sweeps +
+                   update with scratch contents like a workload's; the fastest is kept and handed over zeroed.
+                   `placement` records every candidate's estimated step time and which one was chosen.
     placement_micro_batches : the N the candidates are scored for (weight of the fold sweep in the score).
+    arena_pitch_extra, arena_stagger_bytes : measurement knobs for a slab: 2 MiB units added to the first
+                   pitch tried, and extra bytes (a multiple of 256) between consecutive arenas.
     fold_streams : number of HIP streams (default priority) the folds are spread over: layer l is produced
                    and folded on stream l mod fold_streams, so that the end of one layer's fold overlaps the
                    start of the next one's.  Folds of one layer stay on one stream, hence in order across
@@ -68,8 +78,9 @@ class SimulatedBackward:
     def __init__(self, tensor_sizes: Sequence[int], layers: Sequence[Sequence[int]], gdtype: str,
                  device: str = "cuda:0", stream: torch.cuda.Stream | None = None, pack: str = "aligned",
                  grad_buffer: str = "layer", optimizer: str = "adam", momentum: float = 0.9,
-                 weight_decay: float = 0.0, grad_scale: float = 1.0, arena_stagger_bytes: int | None = None,
-                 fold_streams: int = 1, placement_tries: int = 1, placement_micro_batches: int = 8):
+                 weight_decay: float = 0.0, grad_scale: float = 1.0, arena_layout: str = "slab",
+                 arena_stagger_bytes: int = 0, arena_pitch_extra: int = 0, fold_streams: int = 1,
+                 placement_tries: int = 1, pitch_tries: int = 1, placement_micro_batches: int = 8):
         if gdtype not in _GRAD_BYTES:
             raise ValueError(gdtype)
         if optimizer not in ("adam", "sgdm"):
@@ -120,36 +131,59 @@ class SimulatedBackward:
         if grad_buffer == "layer":
             largest *= fold_streams
         self.grad_buffer_elems = max(largest, 1)
+        if arena_layout not in ("slab", "separate"):
+            raise ValueError(arena_layout)
+        if arena_stagger_bytes % 256 or arena_stagger_bytes < 0 or arena_pitch_extra < 0:
+            raise ValueError("arena_stagger_bytes must be a non-negative multiple of 256, arena_pitch_extra >= 0")
+        if arena_layout == "separate" and (arena_stagger_bytes or arena_pitch_extra or pitch_tries not in (1, [0], (0,))):
+            raise ValueError('arena_stagger_bytes, arena_pitch_extra and pitch_tries apply to arena_layout="slab" only')
+        pitch_extras = list(range(pitch_tries)) if isinstance(pitch_tries, int) else [int(x) for x in pitch_tries]
+        if placement_tries < 1 or not pitch_extras or min(pitch_extras) < 0 or placement_micro_batches < 1:
+            raise ValueError("placement_tries, pitch_tries and placement_micro_batches must be >= 1 (extras >= 0)")
+        self._arena_layout = arena_layout
         self._arena_stagger_bytes = arena_stagger_bytes
-        if placement_tries < 1 or placement_micro_batches < 1:
-            raise ValueError("placement_tries and placement_micro_batches must be >= 1")
-        self._adopt(self._place(placement_tries, placement_micro_batches))
+        self._arena_pitch_extra = arena_pitch_extra
+        self._adopt(self._place(placement_tries, pitch_extras, placement_micro_batches))
 
     # ---- where the state lives ----
-    def _allocate(self) -> dict:
-        """One placement: the arenas, the gradient buffer and the launch lists that point into them."""
-        arena_stagger_bytes, optimizer = self._arena_stagger_bytes, self.optimizer
-        p = {"_slab": None}
+    _TWO_MIB = 1 << 21
+
+    def _pitch(self, j: int) -> int:
+        """Bytes between consecutive arenas of a slab for candidate j: the smallest multiple of 2 MiB that holds an
+        arena (and the stagger), plus arena_pitch_extra + j times 2 MiB."""
+        return (_round_up(self.arena_elems * 4 + 2 * self._arena_stagger_bytes, self._TWO_MIB)
+                + (self._arena_pitch_extra + j) * self._TWO_MIB)
+
+    def _allocate(self, max_extra: int) -> dict:
+        """Device memory for one allocation of the state: the slab (or the separate arenas) and the gradient buffer."""
+        narena = 3 if self.optimizer == "adam" else 2
         with torch.cuda.stream(self.stream):
-            if arena_stagger_bytes is None:
-                p["theta"] = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-                p["m"] = torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-                p["v"] = (torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
-                          if optimizer == "adam" else None)
-            else:
-                # one slab; arena k starts k * stagger bytes past a 2 MiB boundary of the slab, so the
-                # low address bits of m[i], v[i] and theta[i] differ by a chosen amount
-                if arena_stagger_bytes % 256 or arena_stagger_bytes < 0:
-                    raise ValueError("arena_stagger_bytes must be a non-negative multiple of 256")
-                two_mib = 1 << 21
-                pitch = _round_up(self.arena_elems * 4 + 2 * arena_stagger_bytes, two_mib)
-                narena = 3 if optimizer == "adam" else 2
-                p["_slab"] = torch.zeros(narena * pitch + two_mib, dtype=torch.uint8, device=self.device)
-                base = (-p["_slab"].data_ptr()) % two_mib
-                views = [p["_slab"][base + k * (pitch + arena_stagger_bytes):][: self.arena_elems * 4].view(torch.float32)
-                         for k in range(narena)]
-                p["m"], p["v"], p["theta"] = (views[0], views[1], views[2]) if narena == 3 else (views[0], None, views[1])
-        p["grad_buffer"] = torch.empty(self.grad_buffer_elems * self.gbytes, dtype=torch.uint8, device=self.device)
+            if self._arena_layout == "separate":
+                mem = {"arenas": [torch.zeros(self.arena_elems, dtype=torch.float32, device=self.device)
+                                  for _ in range(narena)], "slab": None}
+            else:       # room for the largest pitch that may be tried, and for starting on a 2 MiB boundary
+                mem = {"slab": torch.zeros(narena * self._pitch(max_extra) + self._TWO_MIB, dtype=torch.uint8,
+                                           device=self.device)}
+            mem["grad_buffer"] = torch.empty(self.grad_buffer_elems * self.gbytes, dtype=torch.uint8, device=self.device)
+        return mem
+
+    def _bind(self, mem: dict, j: int) -> dict:
+        """One placement inside an allocation: the arenas (for a slab: at pitch candidate j) and the launch lists that
+        point into them."""
+        optimizer = self.optimizer
+        p = {"_slab": mem["slab"], "_pitch_bytes": None}
+        if mem["slab"] is None:
+            views = mem["arenas"]
+        else:
+            arena_bytes, pitch = self.arena_elems * 4, self._pitch(j)
+            base = (-mem["slab"].data_ptr()) % self._TWO_MIB
+            starts = [base + k * (pitch + self._arena_stagger_bytes) for k in range(3 if optimizer == "adam" else 2)]
+            if starts[-1] + arena_bytes > mem["slab"].numel():
+                raise RuntimeError("arena slab too small for its layout")
+            views = [mem["slab"][o: o + arena_bytes].view(torch.float32) for o in starts]
+            p["_pitch_bytes"] = pitch
+        p["m"], p["v"], p["theta"] = (views[0], views[1], views[2]) if optimizer == "adam" else (views[0], None, views[1])
+        p["grad_buffer"] = mem["grad_buffer"]
         # ---- descriptor lists, built once ----
         gb = p["grad_buffer"].data_ptr()
         if optimizer == "sgdm":
@@ -230,26 +264,42 @@ class SimulatedBackward:
         self.stream.synchronize()
         return total
 
-    def _place(self, tries: int, micro_batches: int) -> dict:
-        best = self._allocate()
-        self.placement = {"tries": 1, "step_ms": [], "chosen": 0}
-        if tries == 1:
-            return best
-        best_ms = self._placement_ms(best, micro_batches)
-        self.placement["step_ms"].append(round(best_ms, 3))
-        for i in range(1, tries):
-            free, _ = torch.cuda.mem_get_info(self.device)
-            if free < self._placement_bytes() * 1.05 + (1 << 30):
-                self.placement["note"] = "a second copy of the state does not fit: stopped"
-                break
-            cand = self._allocate()
-            ms = self._placement_ms(cand, micro_batches)
+    def _place(self, tries: int, pitch_extras: list, micro_batches: int) -> dict:
+        self.placement = {"layout": self._arena_layout, "tries": 0, "pitch_tries": len(pitch_extras), "step_ms": [],
+                          "chosen": [0, 0]}
+        if pitch_extras != list(range(len(pitch_extras))):
+            self.placement["pitch_extras_2mib"] = pitch_extras
+        search = tries > 1 or len(pitch_extras) > 1
+        best, best_ms = None, float("inf")
+        for i in range(tries):
+            if i > 0:
+                free, _ = torch.cuda.mem_get_info(self.device)
+                if free < self._placement_bytes() * 1.05 + (1 << 30):
+                    self.placement["note"] = "a second copy of the state does not fit: stopped"
+                    break
+            mem = self._allocate(max(pitch_extras))
             self.placement["tries"] = i + 1
-            self.placement["step_ms"].append(round(ms, 3))
-            if ms < best_ms:
-                best, best_ms, self.placement["chosen"] = cand, ms, i
-            del cand
-            torch.cuda.empty_cache()                         # hand the loser's memory back to the driver
+            row = []
+            for j, extra in enumerate(pitch_extras):
+                cand = self._bind(mem, extra)
+                if not search:
+                    if cand["_pitch_bytes"] is not None:
+                        self.placement["pitch_2mib"] = cand["_pitch_bytes"] // self._TWO_MIB
+                    return cand
+                ms = self._placement_ms(cand, micro_batches)
+                row.append(round(ms, 3))
+                if ms < best_ms:
+                    best, best_ms, self.placement["chosen"] = cand, ms, [i, j]
+            self.placement["step_ms"].append(row)
+            del mem, cand
+            torch.cuda.empty_cache()                         # hand a loser's memory back to the driver
+        if best["_pitch_bytes"] is not None:
+            self.placement["pitch_2mib"] = best["_pitch_bytes"] // self._TWO_MIB
+        with torch.cuda.stream(self.stream):                 # candidates of one slab overlap: zero the winner last
+            for k in ("theta", "m", "v"):
+                if best[k] is not None:
+                    best[k].zero_()
+        self.stream.synchronize()
         return best
 
     # ---- memory accounting (a4) ----

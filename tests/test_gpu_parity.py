@@ -574,23 +574,30 @@ def test_concurrent_host_threads_on_their_own_streams(torch_cuda):
 
 @pytest.mark.parametrize("optimizer", ["adam", "sgdm"])
 def test_arena_placement_does_not_change_results(torch_cuda, optimizer):
-    """Where the state lives does not change the results: one slab with the arenas staggered against each other
-    (a knob for measuring how relative placement affects bandwidth), or the fastest of three placements the
-    harness tried (placement_tries: it times decay, folds and update on each candidate with scratch contents,
-    keeps the best and hands it over zeroed); bit-identical state after a mini-batch."""
+    """Where the state lives does not change the results: separate allocations, one slab with the arenas a chosen
+    multiple of 2 MiB apart and staggered against each other, or the fastest of the placements the harness tried
+    (placement_tries allocations x pitch_tries pitches inside each slab: it times decay, folds and update on each
+    candidate with scratch contents, keeps the best and hands it over zeroed); bit-identical state after a
+    mini-batch."""
     torch = torch_cuda
     from paper_2305_19982_amd.harness import SimulatedBackward
 
     w = configs.reduced("c3")
     outs = []
-    for stagger, tries in ((None, 1), (0, 1), (4096, 1), (None, 3), (4096, 2)):
-        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, pack="tight", arena_stagger_bytes=stagger,
-                               optimizer=optimizer, placement_tries=tries, placement_micro_batches=w.N)
+    for layout, stagger, extra, tries, pitches in (("separate", 0, 0, 1, 1), ("slab", 0, 0, 1, 1), ("slab", 4096, 0, 1, 1),
+                                                   ("slab", 0, 1, 1, 1), ("separate", 0, 0, 3, 1), ("slab", 4096, 2, 2, 3),
+                                                   ("slab", 0, 0, 1, 4)):
+        hb = SimulatedBackward([t.n for t in w.tensors], w.layers, w.gdtype, pack="tight", arena_layout=layout,
+                               arena_stagger_bytes=stagger, arena_pitch_extra=extra, optimizer=optimizer,
+                               placement_tries=tries, pitch_tries=pitches, placement_micro_batches=w.N)
         hb.synchronize()
-        assert hb.placement["tries"] == tries and len(hb.placement["step_ms"]) == (tries if tries > 1 else 0)
-        assert 0 <= hb.placement["chosen"] < tries
-        if tries > 1:
-            assert hb.placement["step_ms"][hb.placement["chosen"]] == min(hb.placement["step_ms"])
+        pl = hb.placement
+        assert pl["tries"] == tries and pl["pitch_tries"] == pitches
+        searched = tries > 1 or pitches > 1
+        assert [len(row) for row in pl["step_ms"]] == ([pitches] * tries if searched else [])
+        assert 0 <= pl["chosen"][0] < tries and 0 <= pl["chosen"][1] < pitches
+        if searched:
+            assert pl["step_ms"][pl["chosen"][0]][pl["chosen"][1]] == min(min(row) for row in pl["step_ms"])
         for arena in (hb.theta, hb.m, hb.v):
             assert arena is None or not bool(arena.any())            # handed over zeroed
         for t in w.tensors:
@@ -604,9 +611,12 @@ def test_arena_placement_does_not_change_results(torch_cuda, optimizer):
         hb.synchronize()
         kinds = ("theta", "m", "v") if optimizer == "adam" else ("theta", "b")
         outs.append([torch.cat([hb.tensor_view(k, t.index) for t in w.tensors]).clone() for k in kinds])
-        if stagger is not None:
+        if layout == "slab":           # consecutive arenas: the reported pitch (a multiple of 2 MiB) plus the stagger apart
             other = hb.v if optimizer == "adam" else hb.theta
-            assert (other.data_ptr() - hb.m.data_ptr()) % (1 << 21) == stagger
+            first = -(-(hb.arena_elems * 4 + 2 * stagger) // (1 << 21)) + extra
+            assert first <= pl["pitch_2mib"] == first + pl["chosen"][1]
+            assert other.data_ptr() - hb.m.data_ptr() == pl["pitch_2mib"] * (1 << 21) + stagger
+            assert hb.m.data_ptr() % (1 << 21) == 0
     for other in outs[1:]:
         for a, b in zip(outs[0], other):
             assert torch.equal(a, b)
