@@ -14,8 +14,8 @@ and, last, one JSON line with all figures (GB/s of algorithmic bytes).
 
 Ops: fold (12-tensor launches, bf16), single (one 30.7 M-element tensor per launch), fold32 (fp32 gradients, 16-tensor
 BERT-Large-shaped launches of 12.6 M elements), fold_first, fold_last_apply, decay, apply, rescale (whole-state lists),
-sgd_fold, sgd_fold_first, sgd_fold_last_apply, sgd_decay, sgd_apply, and fold@<elements> (one-tensor bf16 fold launches of that
-many elements marching through the arena: the launch-length dependence).  A library built from an older revision of the sources
+sgd_fold, sgd_fold_first, sgd_fold_last_apply, sgd_decay, sgd_apply, and fold@<elements>, fold_first@<elements>,
+sgd_fold@<elements>, sgd_fold_first@<elements> (one-tensor bf16 launches of that many elements marching through the arena: the launch-length dependence).  A library built from an older revision of the sources
 (without adama_debug_set_residency) can be timed with --residency -1.
 """
 from __future__ import annotations
@@ -162,13 +162,23 @@ def main() -> int:
             fn, elems = (lambda: lib.adama_sgdm_begin_step_multi(sgd_state_l, len(sgd_state_l), 0.9, sh)), P
         elif op == "sgd_apply":
             fn, elems = (lambda: lib.adama_sgdm_apply_multi(sgd_state_l, len(sgd_state_l), 0.05, None, sh)), P
-        elif op.startswith("fold@"):
-            n = int(op[5:]) // 4 * 4
+        elif "@" in op and op.split("@")[0] in ("fold", "fold_first", "sgd_fold", "sgd_fold_first"):
+            kind, n = op.split("@")[0], int(op.split("@")[1]) // 4 * 4
             cnt = min(P // n, 400)
             if op not in sized:
-                sized[op] = [B.tensor_list([(mp + 4 * i * n, vp + 4 * i * n, gp + 2 * i * n, n)]) for i in range(cnt)]
-            fn, elems = (lambda: [lib.adama_fold_multi(l, 1, B.BF16, 16, 0.9, 0.999, sh) for l in sized[op]]), n * cnt
-            return 18 * elems / timed(fn) / 1e6
+                if kind.startswith("sgd_"):
+                    sized[op] = [B.sgdm_list([(tp + 4 * i * n, mp + 4 * i * n, gp + 2 * i * n, n)]) for i in range(cnt)]
+                else:
+                    sized[op] = [B.tensor_list([(mp + 4 * i * n, vp + 4 * i * n, gp + 2 * i * n, n)]) for i in range(cnt)]
+            if kind == "fold":
+                fn = lambda: [lib.adama_fold_multi(l, 1, B.BF16, 16, 0.9, 0.999, sh) for l in sized[op]]  # noqa: E731
+            elif kind == "fold_first":
+                fn = lambda: [lib.adama_fold_first_multi(l, 1, B.BF16, 16, 0.9, 0.999, sh) for l in sized[op]]  # noqa: E731
+            elif kind == "sgd_fold":
+                fn = lambda: [lib.adama_sgdm_fold_multi(l, 1, B.BF16, 16, None, sh) for l in sized[op]]  # noqa: E731
+            else:
+                fn = lambda: [lib.adama_sgdm_fold_first_multi(l, 1, B.BF16, 16, 0.9, None, sh) for l in sized[op]]  # noqa: E731
+            return (10 if kind.startswith("sgd_") else 18) * n * cnt / timed(fn) / 1e6
         else:
             raise SystemExit(f"unknown op {op!r}")
         return BYTES[op] * elems / timed(fn) / 1e6

@@ -270,7 +270,7 @@ int adama_residency(int op, unsigned long long launch_elems);
 
 /* Host-only measurement aid, not for production use and not thread-safe: overrides, until the process
  * ends, the number of workgroups per compute unit for launches of op `op` in size class `size_class`
- * (0: under 2^20 elements, 1: up to about 100 M, 2: beyond); wgs_per_cu 0 lifts the bound, -1 restores
+ * (0: under 2^20 elements, 1: under 2^26, 2: from 2^26 on); wgs_per_cu 0 lifts the bound, -1 restores
  * the library's own choice.  Results never depend on it.  Used to produce the A/B tables of the
  * launch policy. */
 void adama_debug_set_residency(int op, int size_class, int wgs_per_cu);

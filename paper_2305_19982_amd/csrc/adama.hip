@@ -62,7 +62,7 @@ constexpr int cache_policy(int op, bool long_launch)
 // a workgroup retires, which beat every persistent grid size tried (2..16 workgroups per CU) by 2..8 %.
 constexpr uint64_t kMaxLaunchElems = ADAMA_MAX_ELEMS;   // keeps the 32-bit chunk numbers of one launch in range
 constexpr uint64_t kBigLaunchElems = 1u << 20;           // "big" launches: at least this many elements
-constexpr uint64_t kHugeLaunchElems = 3u << 25;          // "huge" launches: at least 100.7 M elements
+constexpr uint64_t kHugeLaunchElems = 1u << 26;          // "huge" launches: at least 67.1 M elements
 #ifndef ADAMA_LONG_LAUNCH_ELEMS
 #define ADAMA_LONG_LAUNCH_ELEMS (1u << 23)
 #endif
@@ -74,16 +74,20 @@ constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;   // a policy'
 // blocks (12.6 M .. 315 M elements per launch) and whole-state lists, with realistic array contents
 // (all-zero arrays stream 1..3 % faster and respond differently to every knob below, so they are no guide):
 //  * the folds and the decay stream best through many small workgroups (128 threads x 1 group =
-//    512-element chunks: +0.9 % on 30 M-element launches over 256 x 1, +2 % over 256 x 2, +3.5 % over
-//    256 x 4; a compute unit refills at a finer grain and the grid's tail is shorter), except on launches
-//    beyond about 100 M elements, where 256 x 4 is 0.4 % ahead;
+//    512-element chunks: +2 % on 30 M-element launches over 256 x 1, +4 % over 256 x 2 and 128 x 2; a compute
+//    unit refills at a finer grain and the grid's tail is shorter).  Launches of 2^26 elements and more
+//    ("huge") differ in the residency bound and, for SGD, in shape: the fold 10 workgroups per compute unit
+//    (one-tensor folds of 134 M / 315 M elements: 6619 / 6537 GB/s at 10, 6320 / 6261 unbounded, 5975 / 5863 for
+//    the 256 x 4 these launches used while the stores carried no scope bit), the first fold 13 (6611 / 6532
+//    against 6512 / 6421 unbounded), the SGD folds 128 x 2 at 10 (6547 / 6570 against 6217 / 6023 for 256 x 2,
+//    which stays 2 % ahead at 30 M elements);
 //  * the decay (as many bytes written as read) does best with 128 x 2, in launches of at most 2^26
 //    elements (+4 % on the GPT-2-shaped state over 80-tensor launches of 205 M elements);
 //  * the plain update does best with 256 x 1 (128 x 1 is 3 % slower there, 256 x 4 is 8 % slower: three
 //    read streams and long dependent arithmetic); the fused last fold with 128 x 1 (+0.9 % over 256 x 1);
 //  * the single-moment SGD ops move fewer bytes per element and need two groups per thread to keep
-//    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds, 128 x 2 for decay (+5 %)
-//    and update (+2 %);
+//    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds below 2^26 elements, 128 x 2 for
+//    decay (+5 %) and update (+2 %);
 //  * bounding how many workgroups a compute unit holds (fewer requests in flight) changes the decay, the
 //    update and the edge folds by less than 1 % either way up to the point where the launch becomes
 //    latency-bound and falls off a cliff, so they run unbounded.  The plain fold, whose stores carry the
@@ -99,15 +103,15 @@ struct Policy {
 #ifndef ADAMA_POLICY_TABLE
 #define ADAMA_POLICY_TABLE {                                                            \
     /* decay             */ {{256, 1}, {128, 2}, {128, 2}, ADAMA_DECAY_LAUNCH_CAP},     \
-    /* fold              */ {{256, 1}, {128, 1, 13}, {256, 4}, 0},                          \
+    /* fold              */ {{256, 1}, {128, 1, 13}, {128, 1, 10}, 0},                          \
     /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
-    /* fold_first        */ {{256, 1}, {128, 1}, {256, 4}, 0},                          \
+    /* fold_first        */ {{256, 1}, {128, 1}, {128, 1, 13}, 0},                          \
     /* fold_last_apply   */ {{256, 1}, {128, 1}, {128, 1}, 0},                          \
     /* rescale_apply     */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                    \
     /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
-    /* sgd fold          */ {{256, 1}, {256, 2}, {256, 2}, 0},                          \
+    /* sgd fold          */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
     /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
-    /* sgd fold_first    */ {{256, 1}, {256, 2}, {256, 2}, 0},                          \
+    /* sgd fold_first    */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
     /* sgd fold_last_apply */ {{256, 1}, {256, 2}, {256, 2}, 0},                        \
 }
 #endif

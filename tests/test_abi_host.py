@@ -287,11 +287,14 @@ def test_geometry_misaligned_and_large(lib, op, gdt, gb):
 
 
 def test_geometry_chunk_size_follows_launch_size(lib):
-    """Short launches use 1024-element chunks; the fold moves to larger chunks as launches grow."""
-    sizes = {n: binding.adama_launch_chunk("fold", n) for n in (1, (1 << 20) - 1, 1 << 20, 30_740_800, 3 << 25, 1 << 30)}
+    """Short launches use 1024-element chunks, long ones the op's own shape; the size classes change at 2^20 and
+    2^26 elements, where the residency bound (reported by adama_residency, applied from 2^23 on) may change too."""
+    sizes = {n: binding.adama_launch_chunk("fold", n) for n in (1, (1 << 20) - 1, 1 << 20, 30_740_800, 1 << 26, 1 << 30)}
     assert sizes[1] == sizes[(1 << 20) - 1] == 1024
-    assert sizes[1 << 20] == sizes[30_740_800] and sizes[3 << 25] == sizes[1 << 30]
-    assert sizes[1 << 20] <= sizes[3 << 25]
+    assert sizes[1 << 20] == sizes[30_740_800] and sizes[1 << 26] == sizes[1 << 30]
+    assert binding.adama_residency("fold", (1 << 23) - 1) == 0 < binding.adama_residency("fold", 1 << 23)
+    assert binding.adama_residency("fold", (1 << 26) - 1) == binding.adama_residency("fold", 1 << 23)
+    assert binding.adama_residency("fold", 1 << 26) == binding.adama_residency("fold", 1 << 30) > 0
     assert binding.adama_launch_chunk(99, 5) == 0
     for op in range(11):
         for n in (5, 1 << 22, 1 << 28):
