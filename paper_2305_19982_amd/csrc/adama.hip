@@ -44,11 +44,17 @@ adama_status fail(adama_status st, const char *fmt, ...)
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
 // the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
-// The ops (bit = Op) whose streaming stores also carry the agent-scope bit: the gradient folds.  In-process
-// A/B on the GPT-2-shaped state, with / without: fold +0.5 %, fold with fp32 gradients +0.4 %, first fold
-// +1.7 %, SGD fold +0.6 %; decay -4.7 %, update -2.2 %, rescale -5 %, fused last fold -0.8 %.
+// The ops (bit = Op) whose streaming stores also carry the agent-scope bit.  What it is worth depends on how many
+// workgroups a compute unit holds, so it was measured together with the residency bound (in-process A/B on the
+// GPT-2-shaped state): fold +1.2 %, fold with fp32 gradients +2.2 %, first fold +1.8 %, SGD folds +0.5 % (+5..9 % on
+// launches of 2^26 elements and more), decay +3.2 % (128 x 1 at 10 workgroups per compute unit against 128 x 2
+// plain), fused last fold +2.7 % (128 x 2 at 4), SGD decay +2.0 %, SGD update +3.3 %, SGD fused last fold +4.6 % (128 x 1 at 13
+// against 256 x 2 plain).  The update and the rescale gain
+// nothing from it under any bound (-2..-5 % unbounded) and keep plain non-temporal stores.
 #ifndef ADAMA_SCOPED_STORE_OPS
-#define ADAMA_SCOPED_STORE_OPS ((1 << kFold) | (1 << kFoldFirst) | (1 << kSgdFold) | (1 << kSgdFoldFirst))
+#define ADAMA_SCOPED_STORE_OPS ((1 << kFold) | (1 << kFoldFirst) | (1 << kSgdFold) | (1 << kSgdFoldFirst) | \
+                                (1 << kDecay) | (1 << kFoldLastApply) | (1 << kSgdDecay) | (1 << kSgdApply) | \
+                                (1 << kSgdFoldLastApply))
 #endif
 // Only launches of at least 2^23 elements carry it: a store with the scope bit has to reach memory before its
 // kernel can end, which adds about 2 us to a launch and is paid back by the faster streaming of a long one
@@ -81,20 +87,21 @@ constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;   // a policy'
 //    the 256 x 4 these launches used while the stores carried no scope bit), the first fold 13 (6611 / 6532
 //    against 6512 / 6421 unbounded), the SGD folds 128 x 2 at 10 (6547 / 6570 against 6217 / 6023 for 256 x 2,
 //    which stays 2 % ahead at 30 M elements);
-//  * the decay (as many bytes written as read) does best with 128 x 2, in launches of at most 2^26
-//    elements (+4 % on the GPT-2-shaped state over 80-tensor launches of 205 M elements);
+//  * the decay (as many bytes written as read) does best with 128 x 1 at 10 workgroups per compute unit and
+//    scoped stores (6570 GB/s against 6365 for 128 x 2 unbounded with plain stores), in launches of at most
+//    2^26 elements (+2.4 % over 80-tensor launches of 205 M elements);
 //  * the plain update does best with 256 x 1 (128 x 1 is 3 % slower there, 256 x 4 is 8 % slower: three
-//    read streams and long dependent arithmetic); the fused last fold with 128 x 1 (+0.9 % over 256 x 1);
+//    read streams and long dependent arithmetic); the fused last fold with 128 x 2 at 4 workgroups per
+//    compute unit and scoped stores (6315 against 6150 for 128 x 1 unbounded with plain stores);
 //  * the single-moment SGD ops move fewer bytes per element and need two groups per thread to keep
 //    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds below 2^26 elements, 128 x 2 for
-//    decay (+5 %) and update (+2 %);
-//  * bounding how many workgroups a compute unit holds (fewer requests in flight) changes the decay, the
-//    update and the edge folds by less than 1 % either way up to the point where the launch becomes
-//    latency-bound and falls off a cliff, so they run unbounded.  The plain fold, whose stores carry the
-//    agent-scope bit, gains 0.7..1.0 % with bf16 gradients and 1.7 % with fp32 gradients at 13 workgroups of
-//    128 x 1 (same in three processes; without the scope bit it was flat).  The data-parallel rescale, which
-//    writes three streams, gains 7 % with 4 workgroups of 128 x 2.  Launches under 2^23 elements, which need
-//    every slot to ramp up, stay unbounded;
+//    decay (at 10 workgroups per compute unit) and update (at 8), both with scoped stores;
+//  * bounding how many workgroups a compute unit holds (fewer requests in flight) pays together with scoped
+//    stores (with plain stores every op but the rescale is flat within 1 % until the launch becomes
+//    latency-bound and falls off a cliff): fold 13 (10 from 2^26 elements on), first fold 13 from 2^26 on, decay 10,
+//    fused last fold 4, SGD folds 10 from 2^26 on, SGD decay 10, SGD update 8, SGD fused last fold 13.  The data-parallel rescale, which
+//    writes three streams with plain stores, gains 7 % with 4 workgroups of 128 x 2.  The update runs unbounded.
+//    Launches under 2^23 elements, which need every slot to ramp up, stay unbounded and keep plain stores;
 //  * launches under 2^20 elements are latency-bound and use 256 x 1.
 struct Policy {
     Shape small, big, huge;
@@ -102,17 +109,17 @@ struct Policy {
 };
 #ifndef ADAMA_POLICY_TABLE
 #define ADAMA_POLICY_TABLE {                                                            \
-    /* decay             */ {{256, 1}, {128, 2}, {128, 2}, ADAMA_DECAY_LAUNCH_CAP},     \
+    /* decay             */ {{256, 1}, {128, 1, 10}, {128, 1, 10}, ADAMA_DECAY_LAUNCH_CAP},     \
     /* fold              */ {{256, 1}, {128, 1, 13}, {128, 1, 10}, 0},                          \
     /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
     /* fold_first        */ {{256, 1}, {128, 1}, {128, 1, 13}, 0},                          \
-    /* fold_last_apply   */ {{256, 1}, {128, 1}, {128, 1}, 0},                          \
+    /* fold_last_apply   */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                          \
     /* rescale_apply     */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                    \
-    /* sgd decay         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
+    /* sgd decay         */ {{256, 1}, {128, 2, 10}, {128, 2, 10}, 0},                          \
     /* sgd fold          */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
-    /* sgd apply         */ {{256, 1}, {128, 2}, {128, 2}, 0},                          \
+    /* sgd apply         */ {{256, 1}, {128, 2, 8}, {128, 2, 8}, 0},                          \
     /* sgd fold_first    */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
-    /* sgd fold_last_apply */ {{256, 1}, {256, 2}, {256, 2}, 0},                        \
+    /* sgd fold_last_apply */ {{256, 1}, {128, 1, 13}, {128, 1, 13}, 0},                        \
 }
 #endif
 #ifndef ADAMA_DECAY_LAUNCH_CAP

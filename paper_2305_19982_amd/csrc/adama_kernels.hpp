@@ -81,9 +81,9 @@ __device__ __forceinline__ T ld(const ADAMA_GLOBAL T *p)
 // (ADAMA_STORE_SCOPE): 1 = "sc1 nt" (agent scope), 2 = "sc0 sc1 nt" (system scope), 0 = never, i.e. "nt"
 // alone, which is what __builtin_nontemporal_store emits.  A wider scope than the program needs is always
 // correct: it only tells the caches to write the line through sooner.  Measured on 18 GB of realistic
-// state: with the fold's access mix and none of its arithmetic, stores with sc1 set stream 1.1 % faster
-// than plain non-temporal ones (9 % faster on their own); the folds themselves gain 0.4 .. 1.7 %, while
-// the decay, the update and the rescale lose 2 .. 5 %, so the bit is part of the per-op policy.
+// state: with the fold's access mix and none of its arithmetic, stores with sc1 set stream about 1 % faster
+// than plain non-temporal ones (8 % faster on their own); what the kernels gain depends on the op and on how
+// many workgroups a compute unit holds, so the bit is part of the per-op launch policy.
 #ifndef ADAMA_STORE_SCOPE
 #define ADAMA_STORE_SCOPE 1
 #endif

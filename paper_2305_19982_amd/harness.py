@@ -57,10 +57,11 @@ class SimulatedBackward:
     pitch_tries  : how many pitches to try inside a slab (the smallest that fits, then 2 MiB more each time;
                    default 1), or the list of extras to try, in 2 MiB units (e.g. [0, 1, 64, 65]).  Costs no
                    extra memory beyond the largest extra, so it works for a state that fills the device.
-    placement_tries : how many allocations to try (default 1).  Each further one needs room for a second copy
-                   of the state (the best so far is held, so that the next lands elsewhere); stops early when
-                   there is none.  Every candidate (allocation x pitch) is timed on decay + N fold sweeps +
-                   update with scratch contents like a workload's; the fastest is kept and handed over zeroed.
+    placement_tries : how many allocations to try (default 1).  All of them stay allocated until the search ends
+                   (a freed one would be handed out again), so k tries need room for k copies of the state;
+                   the search stops early when the next copy does not fit.  Every candidate (allocation x pitch)
+                   is timed on decay + N fold sweeps + update with scratch contents like a workload's; the
+                   fastest is kept and handed over zeroed.
                    `placement` records every candidate's estimated step time and which one was chosen.
     placement_micro_batches : the N the candidates are scored for (weight of the fold sweep in the score).
     arena_pitch_extra, arena_stagger_bytes : measurement knobs for a slab: 2 MiB units added to the first
@@ -271,13 +272,15 @@ class SimulatedBackward:
             self.placement["pitch_extras_2mib"] = pitch_extras
         search = tries > 1 or len(pitch_extras) > 1
         best, best_ms = None, float("inf")
-        for i in range(tries):
+        held = []           # every allocation tried stays allocated until the search ends: a freed one would be
+        for i in range(tries):                                # handed out again, and the search would go in circles
             if i > 0:
                 free, _ = torch.cuda.mem_get_info(self.device)
                 if free < self._placement_bytes() * 1.05 + (1 << 30):
-                    self.placement["note"] = "a second copy of the state does not fit: stopped"
+                    self.placement["note"] = "no room for another copy of the state: stopped"
                     break
             mem = self._allocate(max(pitch_extras))
+            held.append(mem)
             self.placement["tries"] = i + 1
             row = []
             for j, extra in enumerate(pitch_extras):
@@ -292,7 +295,8 @@ class SimulatedBackward:
                     best, best_ms, self.placement["chosen"] = cand, ms, [i, j]
             self.placement["step_ms"].append(row)
             del mem, cand
-            torch.cuda.empty_cache()                         # hand a loser's memory back to the driver
+        del held
+        torch.cuda.empty_cache()                             # hand the losers' memory back to the driver
         if best["_pitch_bytes"] is not None:
             self.placement["pitch_2mib"] = best["_pitch_bytes"] // self._TWO_MIB
         with torch.cuda.stream(self.stream):                 # candidates of one slab overlap: zero the winner last
