@@ -260,6 +260,8 @@ int adama_max_tensors_per_launch(void);
  * *big_launch_elems = the launch length from which the op's large-launch shape is used;
  * *policy_bits: 1 = non-temporal gradient loads, 2 = non-temporal state loads, 4 = non-temporal stores,
  * 8 = those stores also carry the agent-scope bit (written through the L2 at once).
+ * Shapes come in three classes of launch length (under 2^20 elements, under 2^26, from 2^26 on); the
+ * residency bound (adama_residency) and bit 8 apply from 2^23 elements per launch on.
  * Any pointer may be NULL. */
 void adama_tuning(int op, unsigned long long launch_elems, int *block, int *groups_per_thread,
                   unsigned long long *big_launch_elems, int *policy_bits);

@@ -42,15 +42,16 @@ adama_status fail(adama_status st, const char *fmt, ...)
 
 // ---- launch policy (measured on MI355X: sweeps over workgroup size, groups per thread, grid shape, cache policy) ----
 // Every byte is touched once per launch and the working set of a layer is far larger than L2 and
-// the memory-side cache, so all streams are marked non-temporal: +13 % over default policy.
+// the memory-side cache, so all streams are marked non-temporal: +12 % over default policy.
 constexpr int kNtPolicy = kNtGradLoad | kNtStateLoad | kNtStore;
-// The ops (bit = Op) whose streaming stores also carry the agent-scope bit.  What it is worth depends on how many
-// workgroups a compute unit holds, so it was measured together with the residency bound (in-process A/B on the
-// GPT-2-shaped state): fold +1.2 %, fold with fp32 gradients +2.2 %, first fold +1.8 %, SGD folds +0.5 % (+5..9 % on
-// launches of 2^26 elements and more), decay +3.2 % (128 x 1 at 10 workgroups per compute unit against 128 x 2
-// plain), fused last fold +2.7 % (128 x 2 at 4), SGD decay +2.0 %, SGD update +3.3 %, SGD fused last fold +4.6 % (128 x 1 at 13
-// against 256 x 2 plain).  The update and the rescale gain
-// nothing from it under any bound (-2..-5 % unbounded) and keep plain non-temporal stores.
+// The ops (bit = Op) whose streaming stores also carry the agent-scope bit.  What it is worth depends on
+// how many workgroups a compute unit holds, so it was measured together with the residency bound
+// (in-process A/B on the GPT-2-shaped state): fold +1.2 %, fold with fp32 gradients +2.2 %, first fold
+// +1.8 %, SGD folds +0.5 % (+5..9 % on launches of 2^26 elements and more), decay +3.2 % (128 x 1 at 10
+// workgroups per compute unit against 128 x 2 plain), fused last fold +2.7 % (128 x 2 at 4), SGD decay
+// +2.0 %, SGD update +3.3 %, SGD fused last fold +4.6 % (128 x 1 at 13 against 256 x 2 plain).  The update
+// and the rescale gain nothing from it under any bound (-2..-5 % unbounded) and keep plain non-temporal
+// stores.
 #ifndef ADAMA_SCOPED_STORE_OPS
 #define ADAMA_SCOPED_STORE_OPS ((1 << kFold) | (1 << kFoldFirst) | (1 << kSgdFold) | (1 << kSgdFoldFirst) | \
                                 (1 << kDecay) | (1 << kFoldLastApply) | (1 << kSgdDecay) | (1 << kSgdApply) | \
@@ -72,7 +73,8 @@ constexpr uint64_t kHugeLaunchElems = 1u << 26;          // "huge" launches: at 
 #ifndef ADAMA_LONG_LAUNCH_ELEMS
 #define ADAMA_LONG_LAUNCH_ELEMS (1u << 23)
 #endif
-constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;   // a policy's residency bound and store scope apply from this launch length on
+// a policy's residency bound and store scope apply from this launch length on
+constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;
 
 // Launch policy per op (index = Op) for small, big and huge launches: threads per workgroup, 16-byte groups
 // per thread, and how many workgroups of the launch a compute unit may hold at once (0: no bound).
@@ -96,30 +98,31 @@ constexpr uint64_t kBoundedLaunchElems = ADAMA_LONG_LAUNCH_ELEMS;   // a policy'
 //  * the single-moment SGD ops move fewer bytes per element and need two groups per thread to keep
 //    enough in flight (128 x 1 costs their fold 13 %): 256 x 2 for the folds below 2^26 elements, 128 x 2 for
 //    decay (at 10 workgroups per compute unit) and update (at 8), both with scoped stores;
-//  * bounding how many workgroups a compute unit holds (fewer requests in flight) pays together with scoped
-//    stores (with plain stores every op but the rescale is flat within 1 % until the launch becomes
-//    latency-bound and falls off a cliff): fold 13 (10 from 2^26 elements on), first fold 13 from 2^26 on, decay 10,
-//    fused last fold 4, SGD folds 10 from 2^26 on, SGD decay 10, SGD update 8, SGD fused last fold 13.  The data-parallel rescale, which
-//    writes three streams with plain stores, gains 7 % with 4 workgroups of 128 x 2.  The update runs unbounded.
-//    Launches under 2^23 elements, which need every slot to ramp up, stay unbounded and keep plain stores;
+//  * bounding how many workgroups a compute unit holds (fewer requests in flight) pays together with
+//    scoped stores (with plain stores every op but the rescale is flat within 1 % until the launch becomes
+//    latency-bound and falls off a cliff): fold 13 (10 from 2^26 elements on), first fold 13 from 2^26 on,
+//    decay 10, fused last fold 4, SGD folds 10 from 2^26 on, SGD decay 10, SGD update 8, SGD fused last
+//    fold 13.  The data-parallel rescale, which writes three streams with plain stores, gains 7 % with 4
+//    workgroups of 128 x 2.  The update runs unbounded.  Launches under 2^23 elements, which need every
+//    slot to ramp up, stay unbounded and keep plain stores;
 //  * launches under 2^20 elements are latency-bound and use 256 x 1.
 struct Policy {
     Shape small, big, huge;
     uint64_t max_launch_elems;   // a list is cut so that no launch of this op exceeds this many elements (0: no such cut)
 };
 #ifndef ADAMA_POLICY_TABLE
-#define ADAMA_POLICY_TABLE {                                                            \
-    /* decay             */ {{256, 1}, {128, 1, 10}, {128, 1, 10}, ADAMA_DECAY_LAUNCH_CAP},     \
-    /* fold              */ {{256, 1}, {128, 1, 13}, {128, 1, 10}, 0},                          \
-    /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                          \
-    /* fold_first        */ {{256, 1}, {128, 1}, {128, 1, 13}, 0},                          \
-    /* fold_last_apply   */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                          \
-    /* rescale_apply     */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                    \
-    /* sgd decay         */ {{256, 1}, {128, 2, 10}, {128, 2, 10}, 0},                          \
-    /* sgd fold          */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
-    /* sgd apply         */ {{256, 1}, {128, 2, 8}, {128, 2, 8}, 0},                          \
-    /* sgd fold_first    */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                          \
-    /* sgd fold_last_apply */ {{256, 1}, {128, 1, 13}, {128, 1, 13}, 0},                        \
+#define ADAMA_POLICY_TABLE {                                                                      \
+    /* decay             */ {{256, 1}, {128, 1, 10}, {128, 1, 10}, ADAMA_DECAY_LAUNCH_CAP},       \
+    /* fold              */ {{256, 1}, {128, 1, 13}, {128, 1, 10}, 0},                            \
+    /* apply             */ {{256, 1}, {256, 1}, {256, 1}, 0},                                    \
+    /* fold_first        */ {{256, 1}, {128, 1}, {128, 1, 13}, 0},                                \
+    /* fold_last_apply   */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                              \
+    /* rescale_apply     */ {{256, 1}, {128, 2, 4}, {128, 2, 4}, 0},                              \
+    /* sgd decay         */ {{256, 1}, {128, 2, 10}, {128, 2, 10}, 0},                            \
+    /* sgd fold          */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                                \
+    /* sgd apply         */ {{256, 1}, {128, 2, 8}, {128, 2, 8}, 0},                              \
+    /* sgd fold_first    */ {{256, 1}, {256, 2}, {128, 2, 10}, 0},                                \
+    /* sgd fold_last_apply */ {{256, 1}, {128, 1, 13}, {128, 1, 13}, 0},                          \
 }
 #endif
 #ifndef ADAMA_DECAY_LAUNCH_CAP
