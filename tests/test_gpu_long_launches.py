@@ -93,3 +93,44 @@ def test_long_launch_equals_short_launches(torch_cuda, n, pre_state, pre_grad):
                 f"{name}: {what} written outside the tensor"
         changed = [not torch.equal(a, base) for a, base in zip(out[0], (theta0, m0, v0))]
         assert any(changed), f"{name} changed nothing"
+
+
+@pytest.mark.parametrize("gdt", ["f32", "bf16", "f16"])
+def test_long_multi_tensor_launch_equals_single_tensor_calls(torch_cuda, gdt):
+    """Seven tensors packed back to back (so most starts are misaligned), none long on its own, together past 2^23
+    elements: the one multi-tensor launch runs under the long-launch policy, the per-tensor calls under the plain one."""
+    torch = torch_cuda
+    from paper_2305_19982_amd import binding
+
+    sizes = [3_000_001, 17, 2_500_003, 999_999, 1_888_889, 5, 1_000_003]
+    total = sum(sizes)
+    assert total >= 1 << 23 and max(sizes) < 1 << 23
+    gb = GBYTES[gdt]
+    gen = torch.Generator(device="cuda:0").manual_seed(total)
+    m0 = torch.empty(total + 8, dtype=torch.float32, device="cuda:0").normal_(0.0, 1e-3, generator=gen)
+    v0 = torch.empty(total + 8, dtype=torch.float32, device="cuda:0").uniform_(1e-9, 1e-5, generator=gen)
+    th0 = torch.empty(total + 8, dtype=torch.float32, device="cuda:0").normal_(0.0, 0.02, generator=gen)
+    g32 = torch.empty(total + 8, dtype=torch.float32, device="cuda:0").normal_(0.0, 1e-2, generator=gen)
+    g = {"f32": g32, "bf16": g32.to(torch.bfloat16), "f16": g32.to(torch.float16)}[gdt]
+    out = []
+    for multi in (True, False):
+        th, m, v = th0.clone(), m0.clone(), v0.clone()
+        fold, upd, off = [], [], 1                    # first tensor one element past an aligned address
+        for n in sizes:
+            fold.append((m.data_ptr() + 4 * off, v.data_ptr() + 4 * off, g.data_ptr() + gb * off, n))
+            upd.append((th.data_ptr() + 4 * off, m.data_ptr() + 4 * off, v.data_ptr() + 4 * off, g.data_ptr() + gb * off, n))
+            off += n
+        if multi:
+            binding.adama_fold_first_multi(fold, None, gdt, N, B1, B2)
+            binding.adama_fold_multi(fold, None, gdt, N, B1, B2)
+            binding.adama_fold_last_apply_multi(upd, None, gdt, N, LR, EPS, B1, B2, T)
+        else:
+            for f, u in zip(fold, upd):
+                binding.adama_fold_first(f[0], f[1], f[2], gdt, f[3], N, B1, B2)
+                binding.adama_fold(f[0], f[1], f[2], gdt, f[3], N, B1, B2)
+                binding.adama_fold_last_apply(u[0], u[1], u[2], u[3], gdt, u[4], N, LR, EPS, B1, B2, T)
+        torch.cuda.synchronize()
+        out.append((th, m, v))
+    for a, b, base in zip(out[0], out[1], (th0, m0, v0)):
+        assert torch.equal(a, b) and not torch.equal(a, base)
+        assert torch.equal(a[:1], base[:1]) and torch.equal(a[1 + total:], base[1 + total:])
