@@ -35,6 +35,8 @@ def test_bench_line_of_a_small_workload_has_every_field():
     assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["extrapolated"] is True and d["cpu_baseline"]["cores"] == 1
     pl = d["arena_placement"]
     assert pl["layout"] == "slab" and pl["tries"] == 2 and [len(r) for r in pl["step_ms"]] == [2, 2]
+    est = pl["estimated_GB/s"]
+    assert est["slowest_candidate"] <= est["first_candidate"] <= est["kept"]
     assert len(d["library_build"]) == 16
 
 
