@@ -374,15 +374,16 @@ def main() -> int:
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
                          "(layer l on stream l mod K; measured: no robust gain); reported as overlapped_folds")
-    ap.add_argument("--placement-tries", type=int, default=8,
+    ap.add_argument("--placement-tries", type=int, default=5,
                     help="allocations of the state the harness may try before the run (untimed set-up; needs room for a "
                          "second copy): the same step runs 2..6 %% faster or slower depending on where the arrays lie; "
                          "every candidate's estimated step time is reported as arena_placement")
     ap.add_argument("--arena-layout", default="slab", choices=["slab", "separate"],
                     help="how the harness lays out theta, m, v: one allocation with the arenas a multiple of 2 MiB apart "
                          "(default), or one allocation per arena")
-    ap.add_argument("--pitch-tries", type=int, default=4,
-                    help="distances between the arenas of a slab the harness may try (2 MiB apart; no extra memory)")
+    ap.add_argument("--pitch-tries", type=int, default=8,
+                    help="distances between the arenas of a slab the harness may try: pairs 2 MiB apart, at the smallest "
+                         "distance that fits and next to the following multiples of 256 MiB (under 1 GB of extra memory)")
     ap.add_argument("--library", default=None,
                     help="run a variant build of the library (python -m paper_2305_19982_amd.build --out ...) instead "
                          "of the package's own, for A/B measurements; the line's library_build then reads \"variant\"")

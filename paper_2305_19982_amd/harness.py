@@ -54,9 +54,11 @@ class SimulatedBackward:
                    or slower from one placement to the next (the fold of GPT-2-XL blocks: 6.37..6.61 TB/s over
                    pitches of one slab that differ by 2 MiB) and stays so for as long as the placement lives.
                    No rule for the distance held up across allocations, so the harness measures:
-    pitch_tries  : how many pitches to try inside a slab (the smallest that fits, then 2 MiB more each time;
-                   default 1), or the list of extras to try, in 2 MiB units (e.g. [0, 1, 64, 65]).  Costs no
-                   extra memory beyond the largest extra, so it works for a state that fills the device.
+    pitch_tries  : how many pitches to try inside a slab (default 1: the smallest that fits; then 2 MiB more, then
+                   pairs of consecutive distances next to the following multiples of 256 MiB, where the effect
+                   of the distance is largest), or the list of extras to try, in 2 MiB units (e.g. [0, 1, 64,
+                   65]).  Costs no extra memory beyond the largest extra (under 1 GB for 8 tries), so it works
+                   for a state that fills the device.
     placement_tries : how many allocations to try (default 1).  All of them stay allocated until the search ends
                    (a freed one would be handed out again), so k tries need room for k copies of the state;
                    the search stops early when the next copy does not fit.  Every candidate (allocation x pitch)
@@ -138,16 +140,34 @@ class SimulatedBackward:
             raise ValueError("arena_stagger_bytes must be a non-negative multiple of 256, arena_pitch_extra >= 0")
         if arena_layout == "separate" and (arena_stagger_bytes or arena_pitch_extra or pitch_tries not in (1, [0], (0,))):
             raise ValueError('arena_stagger_bytes, arena_pitch_extra and pitch_tries apply to arena_layout="slab" only')
-        pitch_extras = list(range(pitch_tries)) if isinstance(pitch_tries, int) else [int(x) for x in pitch_tries]
-        if placement_tries < 1 or not pitch_extras or min(pitch_extras) < 0 or placement_micro_batches < 1:
-            raise ValueError("placement_tries, pitch_tries and placement_micro_batches must be >= 1 (extras >= 0)")
         self._arena_layout = arena_layout
         self._arena_stagger_bytes = arena_stagger_bytes
         self._arena_pitch_extra = arena_pitch_extra
+        pitch_extras = self._pitch_candidates(pitch_tries) if isinstance(pitch_tries, int) else [int(x) for x in pitch_tries]
+        if placement_tries < 1 or not pitch_extras or min(pitch_extras) < 0 or placement_micro_batches < 1:
+            raise ValueError("placement_tries, pitch_tries and placement_micro_batches must be >= 1 (extras >= 0)")
         self._adopt(self._place(placement_tries, pitch_extras, placement_micro_batches))
 
     # ---- where the state lives ----
     _TWO_MIB = 1 << 21
+
+    def _pitch_candidates(self, k: int) -> list:
+        """The first k pitch extras (2 MiB units) worth trying.  Measured on MI355X (fold of GPT-2-XL blocks against the
+        distance d between m and v in 2 MiB units, 1024 consecutive distances in one slab): the rate is a mean plus
+        (-1)^d times a cosine of period 256 in d, so consecutive distances alternate between fast and slow, the
+        difference is largest where d is near a multiple of 128 and vanishes half-way between, and which parity is the
+        fast one flips from one half-period to the next (and was found flipped for a 150 GB state).  Hence pairs of
+        consecutive distances: at the smallest pitch that fits, then next to the following multiples of 128."""
+        if k < 1:
+            return []
+        dmin = _round_up(self.arena_elems * 4 + 2 * self._arena_stagger_bytes, self._TWO_MIB) // self._TWO_MIB \
+            + self._arena_pitch_extra
+        phases, e = [0], (-dmin) % 128
+        while len(phases) * 2 < k:
+            if e not in phases and e - 1 not in phases:
+                phases.append(e)
+            e += 128
+        return [ph + parity for ph in phases for parity in (0, 1)][:k]
 
     def _pitch(self, j: int) -> int:
         """Bytes between consecutive arenas of a slab for candidate j: the smallest multiple of 2 MiB that holds an
@@ -268,8 +288,7 @@ class SimulatedBackward:
     def _place(self, tries: int, pitch_extras: list, micro_batches: int) -> dict:
         self.placement = {"layout": self._arena_layout, "tries": 0, "pitch_tries": len(pitch_extras), "step_ms": [],
                           "chosen": [0, 0]}
-        if pitch_extras != list(range(len(pitch_extras))):
-            self.placement["pitch_extras_2mib"] = pitch_extras
+        self.placement["pitch_extras_2mib"] = pitch_extras
         search = tries > 1 or len(pitch_extras) > 1
         best, best_ms = None, float("inf")
         held = []           # every allocation tried stays allocated until the search ends: a freed one would be

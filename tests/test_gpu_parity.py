@@ -614,7 +614,9 @@ def test_arena_placement_does_not_change_results(torch_cuda, optimizer):
         if layout == "slab":           # consecutive arenas: the reported pitch (a multiple of 2 MiB) plus the stagger apart
             other = hb.v if optimizer == "adam" else hb.theta
             first = -(-(hb.arena_elems * 4 + 2 * stagger) // (1 << 21)) + extra
-            assert first <= pl["pitch_2mib"] == first + pl["chosen"][1]
+            assert pl["pitch_extras_2mib"][:2] == [0, 1][:pitches] and len(pl["pitch_extras_2mib"]) == pitches
+            assert pl["pitch_2mib"] == first + pl["pitch_extras_2mib"][pl["chosen"][1]]
+            assert all((first + x) % 128 in (0, 1) for x in pl["pitch_extras_2mib"][2:])
             assert other.data_ptr() - hb.m.data_ptr() == pl["pitch_2mib"] * (1 << 21) + stagger
             assert hb.m.data_ptr() % (1 << 21) == 0
     for other in outs[1:]:
