@@ -374,7 +374,7 @@ def main() -> int:
     ap.add_argument("--fold-streams", type=int, default=1,
                     help="also time the same mini-batch with the folds of different layers spread over this many streams "
                          "(layer l on stream l mod K; measured: no robust gain); reported as overlapped_folds")
-    ap.add_argument("--placement-tries", type=int, default=5,
+    ap.add_argument("--placement-tries", type=int, default=8,
                     help="allocations of the state the harness may try before the run (untimed set-up; needs room for a "
                          "second copy): the same step runs 2..6 %% faster or slower depending on where the arrays lie; "
                          "every candidate's estimated step time is reported as arena_placement")
