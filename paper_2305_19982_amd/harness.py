@@ -237,6 +237,13 @@ class SimulatedBackward:
     def _placement_bytes(self) -> int:
         return self.arena_elems * 4 * (3 if self.optimizer == "adam" else 2) + self.grad_buffer_elems * self.gbytes
 
+    def _allocation_bytes(self, max_extra: int) -> int:
+        """What _allocate(max_extra) asks the device for."""
+        narena = 3 if self.optimizer == "adam" else 2
+        state = narena * self.arena_elems * 4 if self._arena_layout == "separate" \
+            else narena * self._pitch(max_extra) + self._TWO_MIB
+        return state + self.grad_buffer_elems * self.gbytes
+
     def _placement_ms(self, p: dict, micro_batches: int) -> float:
         """Milliseconds of decay + micro_batches sweeps of folds + update over placement p, its arenas holding values
         like a workload's (what the memory system delivers depends on the contents too); leaves the state zeroed."""
@@ -295,10 +302,16 @@ class SimulatedBackward:
         for i in range(tries):                                # handed out again, and the search would go in circles
             if i > 0:
                 free, _ = torch.cuda.mem_get_info(self.device)
-                if free < self._placement_bytes() * 1.05 + (1 << 30):
+                if free < self._allocation_bytes(max(pitch_extras)) + (1 << 30):
                     self.placement["note"] = "no room for another copy of the state: stopped"
                     break
-            mem = self._allocate(max(pitch_extras))
+            try:
+                mem = self._allocate(max(pitch_extras))
+            except torch.cuda.OutOfMemoryError:
+                if i == 0:
+                    raise
+                self.placement["note"] = "no room for another copy of the state: stopped"
+                break
             held.append(mem)
             self.placement["tries"] = i + 1
             row = []
